@@ -1,0 +1,135 @@
+/*
+ * hstu_attn.h - C ABI of the MI355X (gfx950) jagged HSTU attention library.
+ *
+ * The library computes the attention step and the gated-normalisation step of one
+ * HSTU layer (paper Eq. 3 and Eq. 4) over jagged, variable-length sequences, and
+ * their backward passes (op signatures of the appendix pseudocode of the paper:
+ * attention_forward(q,k,v), attention_backward(dattn,q,k,v),
+ * gated_norm_forward(attn,u,w), gated_norm_backward(dy,attn,u,w)).
+ *
+ * General conventions
+ *   - All tensor pointers are DEVICE pointers unless a comment says HOST.
+ *   - The caller owns every buffer.  The library never allocates, frees or
+ *     synchronises; all work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns immediately.
+ *   - Jagged layout: a batch of B sequences with lengths L_b is stored without
+ *     padding as T = sum L_b token rows; seq_offsets[b] is the first row of
+ *     sequence b and seq_offsets[B] = T.  Q, K, V, A (and gradients) are
+ *     [T, H, d]: element (t, h, c) lives at  base + t*row_stride + h*d + c
+ *     (strides in elements), so the four tensors may be views into one fused
+ *     [T, 4*H*d] buffer (the paper avoids concatenating dU,dQ,dK,dV, Section 4.2.2).
+ *   - Outputs are fully overwritten for every token row of every non-empty
+ *     sequence; nothing is accumulated into them.
+ *   - Every entry point returns an hstu_status; errors are reported through it
+ *     (never by abort/exception) and no kernel is launched on error.
+ *   - B = 0, T = 0 and zero-length sequences are valid: nothing is written for them.
+ */
+#ifndef HSTU_ATTN_H
+#define HSTU_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HSTU_OK = 0,
+  HSTU_ERR_NULL = -1,        /* a required pointer is NULL */
+  HSTU_ERR_SHAPE = -2,       /* negative sizes, strides too small, bad offsets (when a host copy is given) */
+  HSTU_ERR_UNSUPPORTED = -3, /* head_dim / dtype / D outside the supported set */
+  HSTU_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned (256 B) or smaller than *_workspace_bytes */
+  HSTU_ERR_LAUNCH = -5       /* the HIP runtime refused a launch */
+} hstu_status;
+
+typedef enum { HSTU_BF16 = 0, HSTU_FP32 = 1 } hstu_dtype;
+
+/*
+ * Attention problem description (paper Eq. 3 with the masks of Section 4.2.1).
+ *
+ * For sequence b of length L whose last M = num_targets[b] tokens are candidates
+ * (n = L - M history tokens), query row i and key j (0-based inside the sequence):
+ *   hist(p, j)   = j < n && j <= p && (local_window < 0 || p - j < local_window || j < global_prefix)
+ *   history row   i <  n : visible = hist(i, j),             distance = i - j
+ *   candidate row i >= n : visible = (j == i) || hist(n, j), distance = (j == i) ? 0 : n - j
+ *   s = alpha * <Q[i,h,:], K[j,h,:]> + rab_table[h, bucket(distance)]
+ *   A[i,h,:] = sum over visible j of  s * sigmoid(s) * inv_n * V[j,h,:]
+ *   bucket(x) = max{ c : rab_bounds[c] <= x }.
+ * This is the paper's causal mask (local_window < 0) and semi-local mask (local
+ * band of local_window keys including the query itself, plus the first
+ * global_prefix keys of the sequence); local_window = 0 with global_prefix > 0 is
+ * the global-only ablation.  The 1/N factor, the relative-position bias and the
+ * candidate rows are not in the paper's equations; they follow the task's
+ * statement of the layer.
+ */
+typedef struct hstu_attn_params {
+  int32_t batch;            /* B >= 0 */
+  int32_t num_heads;        /* H in [1, 256] */
+  int32_t head_dim;         /* d = d_qk = d_v: 32, 64 or 128 */
+  int32_t total_tokens;     /* T = seq_offsets[B] */
+  int32_t max_seqlen;       /* >= max_b L_b; sizes the expanded bias table and index ranges */
+  int32_t dtype;            /* hstu_dtype of q, k, v, out, dout, dq, dk, dv */
+  int64_t row_stride_q;     /* elements between consecutive tokens of q (and of dq); >= H*d */
+  int64_t row_stride_k;     /* same for k / dk */
+  int64_t row_stride_v;     /* same for v / dv */
+  int64_t row_stride_o;     /* same for out / dout */
+  const int32_t* seq_offsets;      /* DEVICE int32[B+1], [0] = 0, non-decreasing */
+  const int32_t* seq_offsets_host; /* HOST copy of the same, or NULL; when given it is validated */
+  const int32_t* num_targets;      /* DEVICE int32[B] (0 <= M_b <= L_b) or NULL = no candidates */
+  int32_t local_window;     /* K1: < 0 dense causal; >= 0 keys with 0 <= p - j < K1 */
+  int32_t global_prefix;    /* K2 >= 0: keys j < K2 (ignored when local_window < 0) */
+  float alpha;              /* multiplies QK^T; the paper has none (1.0) */
+  float inv_n;              /* 1/N applied after SiLU */
+  const float* rab_table;   /* DEVICE fp32[H, num_buckets] or NULL = no bias */
+  const int32_t* rab_bounds;/* DEVICE int32[num_buckets], strictly increasing, [0] = 0 (NULL iff rab_table NULL) */
+  int32_t num_buckets;      /* in [1, 4096] when rab_table is given */
+} hstu_attn_params;
+
+/* Bytes of device scratch (256-byte aligned) that hstu_attn_fwd (for_backward = 0)
+ * or hstu_attn_bwd (for_backward != 0) needs for this problem.  Depends only on
+ * batch, num_heads, head_dim, total_tokens, max_seqlen and dtype.  Returns 0 for an
+ * invalid description (the compute call then reports the error). */
+size_t hstu_attn_workspace_bytes(const hstu_attn_params* p, int for_backward);
+
+/* Paper Eq. 3, forward (attention_forward of the appendix pseudocode).
+ * q, k, v: inputs [T, H, d]; out: A [T, H, d]; all DEVICE, dtype p->dtype.
+ * Enqueues: tile scheduler (skips fully masked blocks), bias expansion, attention kernel. */
+int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, void* out,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of Eq. 3 (attention_backward(dattn, q, k, v) -> dq, dk, dv): the scores are
+ * recomputed from q, k; nothing saved by the forward is needed.  dout uses row_stride_o,
+ * dq/dk/dv use the strides of q/k/v.  The bias table receives no gradient. */
+int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, const void* dout,
+                  void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Paper Eq. 4 without f2 (gated_norm_forward): Y = (LayerNorm_D(A) * gamma + beta) * U, the layer
+ * norm taken over the D = H*d features of a token (biased variance, eps inside the square root).
+ * attn, u, y: [T, D] contiguous, dtype `dtype`; gamma: fp32[D]; beta: fp32[D] or NULL (= 0);
+ * mean, rstd: fp32[T] outputs or NULL.  D must be a multiple of 8 and at most 8192. */
+int hstu_gated_norm_fwd(int64_t T, int32_t D, int32_t dtype, const void* attn, const void* u, const float* gamma,
+                        const float* beta, float eps, void* y, float* mean, float* rstd, void* stream);
+
+/* Bytes of scratch hstu_gated_norm_bwd needs (partial column sums for dgamma/dbeta). */
+size_t hstu_gated_norm_bwd_workspace_bytes(int64_t T, int32_t D);
+
+/* gated_norm_backward(dy, attn, u, w) -> dattn, du, dw: recomputes the normalised A.
+ * dattn, du: [T, D] dtype `dtype`; dgamma: fp32[D]; dbeta: fp32[D] or NULL.  Deterministic. */
+int hstu_gated_norm_bwd(int64_t T, int32_t D, int32_t dtype, const void* dy, const void* attn, const void* u,
+                        const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
+                        float* dbeta, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Human-readable name of a status code (static storage). */
+const char* hstu_status_string(int status);
+
+/* Statistics of the last tile schedule written by hstu_attn_fwd/bwd into `workspace`
+ * (valid after the stream has been synchronised): HOST out[0] = scheduled row blocks x heads,
+ * out[1] = scheduled (row block, column block) tiles x heads, out[2] = tiles a dense L x L
+ * grid would have.  Reads device memory with a blocking copy; for reporting only. */
+int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, int for_backward, int64_t out[3]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HSTU_ATTN_H */

@@ -1,0 +1,174 @@
+"""Thin ctypes binding of ``libhstu_attn.so`` (C ABI: include/hstu_attn.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch supplies device memory and streams.  There is no CPU fallback:
+importing this module without the built library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhstu_attn.so")
+
+HSTU_BF16, HSTU_FP32 = 0, 1
+HSTU_OK = 0
+
+
+class HstuError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+class HstuAttnParams(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("total_tokens", ctypes.c_int32), ("max_seqlen", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("row_stride_q", ctypes.c_int64), ("row_stride_k", ctypes.c_int64),
+        ("row_stride_v", ctypes.c_int64), ("row_stride_o", ctypes.c_int64),
+        ("seq_offsets", ctypes.c_void_p), ("seq_offsets_host", ctypes.c_void_p), ("num_targets", ctypes.c_void_p),
+        ("local_window", ctypes.c_int32), ("global_prefix", ctypes.c_int32),
+        ("alpha", ctypes.c_float), ("inv_n", ctypes.c_float),
+        ("rab_table", ctypes.c_void_p), ("rab_bounds", ctypes.c_void_p), ("num_buckets", ctypes.c_int32),
+    ]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2602_16986_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32, i64, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    pp = ctypes.POINTER(HstuAttnParams)
+    lib.hstu_status_string.restype = ctypes.c_char_p
+    lib.hstu_status_string.argtypes = [ctypes.c_int]
+    lib.hstu_attn_workspace_bytes.restype = sz
+    lib.hstu_attn_workspace_bytes.argtypes = [pp, ctypes.c_int]
+    lib.hstu_attn_fwd.restype = ctypes.c_int
+    lib.hstu_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
+    lib.hstu_attn_bwd.restype = ctypes.c_int
+    lib.hstu_attn_bwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.hstu_attn_schedule_stats.restype = ctypes.c_int
+    lib.hstu_attn_schedule_stats.argtypes = [pp, vp, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
+    lib.hstu_gated_norm_fwd.restype = ctypes.c_int
+    lib.hstu_gated_norm_fwd.argtypes = [i64, i32, i32, vp, vp, vp, vp, f32, vp, vp, vp, vp]
+    lib.hstu_gated_norm_bwd_workspace_bytes.restype = sz
+    lib.hstu_gated_norm_bwd_workspace_bytes.argtypes = [i64, i32]
+    lib.hstu_gated_norm_bwd.restype = ctypes.c_int
+    lib.hstu_gated_norm_bwd.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
+    return lib
+
+
+_lib = _load()
+EXPORTS = ["hstu_attn_workspace_bytes", "hstu_attn_fwd", "hstu_attn_bwd", "hstu_gated_norm_fwd",
+           "hstu_gated_norm_bwd_workspace_bytes", "hstu_gated_norm_bwd", "hstu_status_string",
+           "hstu_attn_schedule_stats"]
+
+
+def status_string(status: int) -> str:
+    return _lib.hstu_status_string(int(status)).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return HSTU_BF16
+    if t.dtype == torch.float32:
+        return HSTU_FP32
+    raise HstuError(-3, f"dtype {t.dtype}")
+
+
+class AttnProblem:
+    """Owns an ``hstu_attn_params`` struct and keeps the tensors it points to alive."""
+
+    def __init__(self, q, k, v, out_like, seq_offsets, *, max_seqlen, seq_offsets_host=None, num_targets=None,
+                 local_window=-1, global_prefix=0, alpha=1.0, inv_n=1.0, rab_table=None, rab_bounds=None):
+        T, H, d = q.shape
+        self._keep = (seq_offsets, num_targets, rab_table, rab_bounds)
+        self._host = None if seq_offsets_host is None else np.ascontiguousarray(seq_offsets_host, dtype=np.int32)
+        p = HstuAttnParams()
+        p.batch = int(seq_offsets.shape[0]) - 1
+        p.num_heads, p.head_dim, p.total_tokens, p.max_seqlen = H, d, T, int(max_seqlen)
+        p.dtype = _dtype_code(q)
+        for name, t in (("q", q), ("k", k), ("v", v), ("o", out_like)):
+            assert t.stride(2) == 1 and t.stride(1) == d, "head stride must be d, features contiguous"
+            setattr(p, f"row_stride_{name}", t.stride(0) if T > 0 else H * d)
+        p.seq_offsets = _ptr(seq_offsets)
+        p.seq_offsets_host = None if self._host is None else self._host.ctypes.data
+        p.num_targets = _ptr(num_targets)
+        p.local_window, p.global_prefix = int(local_window), int(global_prefix)
+        p.alpha, p.inv_n = float(alpha), float(inv_n)
+        p.rab_table, p.rab_bounds = _ptr(rab_table), _ptr(rab_bounds)
+        p.num_buckets = 0 if rab_bounds is None else int(rab_bounds.shape[0])
+        self.params = p
+
+    def ref(self):
+        return ctypes.byref(self.params)
+
+
+def hstu_attn_workspace_bytes(prob: AttnProblem, for_backward: bool) -> int:
+    return int(_lib.hstu_attn_workspace_bytes(prob.ref(), 1 if for_backward else 0))
+
+
+def new_workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def hstu_attn_fwd(prob: AttnProblem, q, k, v, out, workspace: torch.Tensor, stream=None) -> None:
+    st = _lib.hstu_attn_fwd(prob.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(workspace), workspace.numel(),
+                            _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_attn_fwd")
+
+
+def hstu_attn_bwd(prob: AttnProblem, q, k, v, dout, dq, dk, dv, workspace: torch.Tensor, stream=None) -> None:
+    st = _lib.hstu_attn_bwd(prob.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv),
+                            _ptr(workspace), workspace.numel(), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_attn_bwd")
+
+
+def hstu_attn_schedule_stats(prob: AttnProblem, workspace: torch.Tensor, for_backward: bool = False):
+    out = (ctypes.c_int64 * 3)()
+    st = _lib.hstu_attn_schedule_stats(prob.ref(), _ptr(workspace), 1 if for_backward else 0, out)
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_attn_schedule_stats")
+    return {"items": int(out[0]), "tiles": int(out[1]), "dense_tiles": int(out[2])}
+
+
+def hstu_gated_norm_fwd(attn, u, gamma, beta, eps, y, mean=None, rstd=None, stream=None) -> None:
+    T = attn.shape[0]
+    D = attn.numel() // T if T else int(np.prod(attn.shape[1:]))
+    st = _lib.hstu_gated_norm_fwd(T, D, _dtype_code(attn), _ptr(attn), _ptr(u), _ptr(gamma), _ptr(beta), float(eps),
+                                  _ptr(y), _ptr(mean), _ptr(rstd), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_gated_norm_fwd")
+
+
+def hstu_gated_norm_bwd_workspace_bytes(T: int, D: int) -> int:
+    return int(_lib.hstu_gated_norm_bwd_workspace_bytes(T, D))
+
+
+def hstu_gated_norm_bwd(dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta, workspace, stream=None) -> None:
+    T = attn.shape[0]
+    D = attn.numel() // T if T else int(np.prod(attn.shape[1:]))
+    st = _lib.hstu_gated_norm_bwd(T, D, _dtype_code(attn), _ptr(dy), _ptr(attn), _ptr(u), _ptr(gamma), _ptr(beta),
+                                  float(eps), _ptr(dattn), _ptr(du), _ptr(dgamma), _ptr(dbeta), _ptr(workspace),
+                                  workspace.numel(), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_gated_norm_bwd")

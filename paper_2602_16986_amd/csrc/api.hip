@@ -1,0 +1,228 @@
+// C-ABI entry points of the jagged HSTU attention library: argument validation, workspace
+// layout and kernel launches.  Declarations and the meaning of every argument: include/hstu_attn.h.
+#include "../../include/hstu_attn.h"
+#include "hstu_common.h"
+#include "hstu_kernels.h"
+
+using namespace hstu;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Upper bound of the schedule length: every sequence adds at most one ragged block.
+inline int64_t max_items_for(const hstu_attn_params* p, int block_rows) {
+  return ((int64_t)p->total_tokens / block_rows + p->batch) * p->num_heads;
+}
+
+struct Layout {           // byte offsets inside a workspace
+  size_t header[2], items[2], seq_base[2], bias, total;
+  int max_items[2];
+};
+
+// One schedule for the forward; two (dQ pass, dK/dV pass) for the backward.
+Layout make_layout(const hstu_attn_params* p, int for_backward) {
+  Layout l = {};
+  size_t off = 0;
+  const int nsched = for_backward ? 2 : 1;
+  for (int s = 0; s < nsched; ++s) {
+    const int rows = !for_backward ? fwd_block_rows(p->dtype, p->head_dim)
+                                   : (s == 0 ? dq_block_rows(p->dtype, p->head_dim) : dkv_block_rows(p->dtype, p->head_dim));
+    l.max_items[s] = (int)max_items_for(p, rows);
+    l.header[s] = off; off += kAlign;
+    l.items[s] = off; off += align_up((size_t)l.max_items[s] * sizeof(WorkItem));
+    l.seq_base[s] = off; off += align_up(((size_t)p->batch + 1) * sizeof(int32_t));
+  }
+  l.bias = off;
+  off += align_up((size_t)p->num_heads * ((size_t)p->max_seqlen + 1) * sizeof(float));
+  l.total = off;
+  return l;
+}
+
+int validate(const hstu_attn_params* p) {
+  if (!p) return HSTU_ERR_NULL;
+  if (p->batch < 0 || p->total_tokens < 0 || p->max_seqlen < 0 || p->num_heads < 1 || p->num_heads > 256) return HSTU_ERR_SHAPE;
+  if (p->dtype != HSTU_BF16 && p->dtype != HSTU_FP32) return HSTU_ERR_UNSUPPORTED;
+  if (p->head_dim != 32 && p->head_dim != 64 && p->head_dim != 128) return HSTU_ERR_UNSUPPORTED;
+  const int64_t hd = (int64_t)p->num_heads * p->head_dim;
+  const int64_t quantum = p->dtype == HSTU_BF16 ? 8 : 4;     // rows must start on 16-byte boundaries
+  const int64_t strides[4] = {p->row_stride_q, p->row_stride_k, p->row_stride_v, p->row_stride_o};
+  for (int i = 0; i < 4; ++i)
+    if (strides[i] < hd || strides[i] % quantum != 0) return HSTU_ERR_SHAPE;
+  if (p->batch > 0 && !p->seq_offsets) return HSTU_ERR_NULL;
+  if (p->global_prefix < 0) return HSTU_ERR_SHAPE;
+  if ((p->rab_table == nullptr) != (p->rab_bounds == nullptr)) return HSTU_ERR_NULL;
+  if (p->rab_table && (p->num_buckets < 1 || p->num_buckets > 4096)) return HSTU_ERR_SHAPE;
+  if ((int64_t)p->total_tokens * p->num_heads / 32 + (int64_t)p->batch * p->num_heads > 0x7FFFFF00) return HSTU_ERR_SHAPE;
+  if (p->seq_offsets_host) {
+    const int32_t* o = p->seq_offsets_host;
+    if (o[0] != 0) return HSTU_ERR_SHAPE;
+    for (int b = 0; b < p->batch; ++b) {
+      const int64_t len = (int64_t)o[b + 1] - o[b];
+      if (len < 0 || len > p->max_seqlen) return HSTU_ERR_SHAPE;
+    }
+    if (o[p->batch] != p->total_tokens) return HSTU_ERR_SHAPE;
+  }
+  return HSTU_OK;
+}
+
+inline bool misaligned(const void* ptr) { return ((uintptr_t)ptr & 15u) != 0; }
+
+AttnArgs make_args(const hstu_attn_params* p, const void* q, const void* k, const void* v) {
+  AttnArgs a = {};
+  a.q = q; a.k = k; a.v = v;
+  a.sq = p->row_stride_q; a.sk = p->row_stride_k; a.sv = p->row_stride_v; a.so = p->row_stride_o;
+  a.offsets = p->seq_offsets; a.num_targets = p->num_targets;
+  a.B = p->batch; a.H = p->num_heads; a.D = p->head_dim; a.T = p->total_tokens; a.max_seqlen = p->max_seqlen;
+  a.K1 = p->local_window < 0 ? -1 : p->local_window;
+  a.K2 = p->global_prefix;
+  a.alpha = p->alpha; a.inv_n = p->inv_n;
+  return a;
+}
+
+// Enqueues the bias expansion (if any) and fills the bias fields.
+hipError_t prepare_bias(const hstu_attn_params* p, AttnArgs& a, unsigned char* ws, const Layout& l, hipStream_t stream) {
+  a.bias = nullptr;
+  a.bias_stride = p->max_seqlen + 1;
+  if (!p->rab_table) return hipSuccess;
+  float* bias = (float*)(ws + l.bias);
+  a.bias = bias;
+  return launch_bias_expand(p->rab_table, p->rab_bounds, p->num_buckets, p->num_heads, a.bias_stride, bias, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hstu_status_string(int status) {
+  switch (status) {
+    case HSTU_OK: return "HSTU_OK";
+    case HSTU_ERR_NULL: return "HSTU_ERR_NULL: required pointer is NULL";
+    case HSTU_ERR_SHAPE: return "HSTU_ERR_SHAPE: invalid sizes, strides, alignment or offsets";
+    case HSTU_ERR_UNSUPPORTED: return "HSTU_ERR_UNSUPPORTED: head_dim, dtype or feature count not supported";
+    case HSTU_ERR_WORKSPACE: return "HSTU_ERR_WORKSPACE: workspace missing, misaligned or too small";
+    case HSTU_ERR_LAUNCH: return "HSTU_ERR_LAUNCH: HIP runtime refused a launch";
+    default: return "unknown hstu_status";
+  }
+}
+
+size_t hstu_attn_workspace_bytes(const hstu_attn_params* p, int for_backward) {
+  if (validate(p) != HSTU_OK) return 0;
+  return make_layout(p, for_backward).total;
+}
+
+int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, void* out, void* workspace,
+                  size_t workspace_bytes, void* stream_) {
+  const int st = validate(p);
+  if (st != HSTU_OK) return st;
+  if (p->total_tokens == 0 || p->batch == 0) return HSTU_OK;
+  if (!q || !k || !v || !out) return HSTU_ERR_NULL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out)) return HSTU_ERR_SHAPE;
+  const Layout l = make_layout(p, 0);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < l.total) return HSTU_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)stream_;
+  unsigned char* ws = (unsigned char*)workspace;
+
+  AttnArgs a = make_args(p, q, k, v);
+  a.out = out;
+  a.max_items = l.max_items[0];
+  a.header = (const SchedHeader*)(ws + l.header[0]);
+  a.items = (const WorkItem*)(ws + l.items[0]);
+  if (launch_schedule(a, fwd_block_rows(p->dtype, p->head_dim), stream_tile_rows(p->dtype, p->head_dim), false,
+                      (SchedHeader*)(ws + l.header[0]), (WorkItem*)(ws + l.items[0]), (int32_t*)(ws + l.seq_base[0]),
+                      stream) != hipSuccess)
+    return HSTU_ERR_LAUNCH;
+  if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  if (launch_attn_fwd(a, p->dtype, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
+int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, const void* dout, void* dq,
+                  void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream_) {
+  const int st = validate(p);
+  if (st != HSTU_OK) return st;
+  if (p->total_tokens == 0 || p->batch == 0) return HSTU_OK;
+  if (!q || !k || !v || !dout || !dq || !dk || !dv) return HSTU_ERR_NULL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(dout) || misaligned(dq) || misaligned(dk) ||
+      misaligned(dv))
+    return HSTU_ERR_SHAPE;
+  const Layout l = make_layout(p, 1);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < l.total) return HSTU_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)stream_;
+  unsigned char* ws = (unsigned char*)workspace;
+
+  AttnArgs a = make_args(p, q, k, v);
+  a.dout = dout; a.dq = dq; a.dk = dk; a.dv = dv;
+  const int tile = stream_tile_rows(p->dtype, p->head_dim);
+  if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  for (int s = 0; s < 2; ++s) {                          // s = 0: dQ pass (query blocks), s = 1: dK/dV pass (key blocks)
+    a.max_items = l.max_items[s];
+    a.header = (const SchedHeader*)(ws + l.header[s]);
+    a.items = (const WorkItem*)(ws + l.items[s]);
+    const int rows = s == 0 ? dq_block_rows(p->dtype, p->head_dim) : dkv_block_rows(p->dtype, p->head_dim);
+    if (launch_schedule(a, rows, tile, s == 1, (SchedHeader*)(ws + l.header[s]), (WorkItem*)(ws + l.items[s]),
+                        (int32_t*)(ws + l.seq_base[s]), stream) != hipSuccess)
+      return HSTU_ERR_LAUNCH;
+    const hipError_t e = s == 0 ? launch_attn_bwd_dq(a, p->dtype, stream) : launch_attn_bwd_dkdv(a, p->dtype, stream);
+    if (e != hipSuccess) return HSTU_ERR_LAUNCH;
+  }
+  return HSTU_OK;
+}
+
+int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, int for_backward, int64_t out[3]) {
+  const int st = validate(p);
+  if (st != HSTU_OK) return st;
+  if (!workspace || !out) return HSTU_ERR_NULL;
+  const Layout l = make_layout(p, for_backward);
+  SchedHeader h;
+  if (hipMemcpy(&h, (const unsigned char*)workspace + l.header[0], sizeof(h), hipMemcpyDeviceToHost) != hipSuccess)
+    return HSTU_ERR_LAUNCH;
+  out[0] = h.count; out[1] = h.tiles; out[2] = h.dense_tiles;
+  return HSTU_OK;
+}
+
+static int validate_norm(int64_t T, int32_t D, int32_t dtype) {
+  if (T < 0 || D < 1) return HSTU_ERR_SHAPE;
+  if (dtype != HSTU_BF16 && dtype != HSTU_FP32) return HSTU_ERR_UNSUPPORTED;
+  if (D % 8 != 0 || D > 8192) return HSTU_ERR_UNSUPPORTED;
+  return HSTU_OK;
+}
+
+int hstu_gated_norm_fwd(int64_t T, int32_t D, int32_t dtype, const void* attn, const void* u, const float* gamma,
+                        const float* beta, float eps, void* y, float* mean, float* rstd, void* stream) {
+  const int st = validate_norm(T, D, dtype);
+  if (st != HSTU_OK) return st;
+  if (T == 0) return HSTU_OK;
+  if (!attn || !u || !gamma || !y) return HSTU_ERR_NULL;
+  if (misaligned(attn) || misaligned(u) || misaligned(gamma) || misaligned(y) || (beta && misaligned(beta))) return HSTU_ERR_SHAPE;
+  if (launch_gated_norm_fwd(T, D, dtype, attn, u, gamma, beta, eps, y, mean, rstd, (hipStream_t)stream) != hipSuccess)
+    return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
+size_t hstu_gated_norm_bwd_workspace_bytes(int64_t T, int32_t D) {
+  if (T < 0 || D < 1) return 0;
+  const size_t blocks = (size_t)gated_norm_bwd_blocks(T);
+  return align_up((blocks > 0 ? blocks : 1) * 2 * (size_t)D * sizeof(float));
+}
+
+int hstu_gated_norm_bwd(int64_t T, int32_t D, int32_t dtype, const void* dy, const void* attn, const void* u,
+                        const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
+                        float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+  const int st = validate_norm(T, D, dtype);
+  if (st != HSTU_OK) return st;
+  if (!gamma || !dgamma) return HSTU_ERR_NULL;
+  if (T > 0 && (!dy || !attn || !u || !dattn || !du)) return HSTU_ERR_NULL;
+  if (misaligned(dy) || misaligned(attn) || misaligned(u) || misaligned(gamma) || misaligned(dattn) || misaligned(du) ||
+      (beta && misaligned(beta)))
+    return HSTU_ERR_SHAPE;
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < hstu_gated_norm_bwd_workspace_bytes(T, D))
+    return HSTU_ERR_WORKSPACE;
+  if (launch_gated_norm_bwd(T, D, dtype, dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta, (float*)workspace,
+                            (hipStream_t)stream) != hipSuccess)
+    return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,301 @@
+// U-gated layer normalisation after the attention (paper Eq. 4 without the f2 projection):
+//   Y = (LayerNorm_D(A) * gamma + beta) * U          over the D = H*d features of each token
+// and its backward (gated_norm_backward of the paper's appendix pseudocode, which recomputes the
+// normalised activations instead of saving them).  Both passes are HBM-bound streaming kernels:
+// one wavefront per token row, 16-byte loads per lane, wave-level reductions through DPP
+// shuffles, everything between the load and the store in registers.
+#include "hstu_common.h"
+#include "hstu_kernels.h"
+
+namespace hstu {
+
+constexpr int kRowsPerBlock = 4;        // one wave per row, 4 waves per workgroup
+constexpr int kMaxBwdBlocks = 2048;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+// 8 consecutive elements starting at element index e0 of a row, widened to fp32
+template <typename E>
+__device__ __forceinline__ void load8(const E* row, int e0, float (&v)[8]) {
+  if constexpr (sizeof(E) == 2) {
+    const u32x4 raw = *(const u32x4*)(row + e0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(raw[i] << 16);
+      v[2 * i + 1] = __uint_as_float(raw[i] & 0xFFFF0000u);
+    }
+  } else {
+    const f32x4 a = *(const f32x4*)(row + e0), b = *(const f32x4*)(row + e0 + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+  }
+}
+
+template <typename E>
+__device__ __forceinline__ void store8(E* row, int e0, const float (&v)[8]) {
+  if constexpr (sizeof(E) == 2) {
+    *(u32x4*)(row + e0) = (u32x4){pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                                  pack_bf16x2(v[6], v[7])};
+  } else {
+    *(f32x4*)(row + e0) = (f32x4){v[0], v[1], v[2], v[3]};
+    *(f32x4*)(row + e0 + 4) = (f32x4){v[4], v[5], v[6], v[7]};
+  }
+}
+
+// mean and reciprocal standard deviation of one row held as NCH chunks of 8 per lane
+template <int NCH>
+__device__ __forceinline__ void row_stats(const float (&a)[NCH][8], int lane, int D, float eps, float& mu, float& rs) {
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c)
+    if ((lane + 64 * c) * 8 < D)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += a[c][i];
+  mu = wave_sum(s) / (float)D;
+  float q = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c)
+    if ((lane + 64 * c) * 8 < D)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { const float dlt = a[c][i] - mu; q += dlt * dlt; }
+  const float var = wave_sum(q) / (float)D;
+  rs = 1.0f / sqrtf(var + eps);
+}
+
+template <typename E, int NCH>
+__global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_fwd_kernel(int64_t T, int D, const E* __restrict__ attn,
+                                                                            const E* __restrict__ u,
+                                                                            const float* __restrict__ gamma,
+                                                                            const float* __restrict__ beta, float eps,
+                                                                            E* __restrict__ y, float* __restrict__ mean,
+                                                                            float* __restrict__ rstd) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave;
+  if (row >= T) return;
+  const E* arow = attn + row * D;
+  const E* urow = u + row * D;
+  E* yrow = y + row * D;
+  float a[NCH][8];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int e0 = (lane + 64 * c) * 8;
+    if (e0 < D) load8(arow, e0, a[c]);
+  }
+  float mu, rs;
+  row_stats<NCH>(a, lane, D, eps, mu, rs);
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int e0 = (lane + 64 * c) * 8;
+    if (e0 < D) {
+      float uv[8], gv[8], bv[8], out[8];
+      load8(urow, e0, uv);
+      load8(gamma, e0, gv);
+      if (beta) load8(beta, e0, bv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out[i] = ((a[c][i] - mu) * rs * gv[i] + (beta ? bv[i] : 0.f)) * uv[i];
+      store8(yrow, e0, out);
+    }
+  }
+  if (lane == 0) {
+    if (mean) mean[row] = mu;
+    if (rstd) rstd[row] = rs;
+  }
+}
+
+// Backward.  Per row: ahat = (a - mu) rstd, dn = dy u, dU = dy (ahat gamma + beta), dahat = dn gamma,
+// dA = rstd (dahat - mean(dahat) - ahat mean(dahat ahat)).  Column sums dgamma = sum dn ahat and
+// dbeta = sum dn are kept per lane over the rows a wave visits, combined across the workgroup's
+// waves in a fixed order through LDS and written as one partial row per workgroup.
+template <typename E, int NCH>
+__global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_bwd_kernel(int64_t T, int D, const E* __restrict__ dy,
+                                                                            const E* __restrict__ attn,
+                                                                            const E* __restrict__ u,
+                                                                            const float* __restrict__ gamma,
+                                                                            const float* __restrict__ beta, float eps,
+                                                                            E* __restrict__ dattn, E* __restrict__ du,
+                                                                            float* __restrict__ partial) {
+  extern __shared__ float red[];                       // [2][D]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float gsum[NCH][8], bsum[NCH][8], gv[NCH][8], bv[NCH][8];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int e0 = (lane + 64 * c) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; gv[c][i] = 0.f; bv[c][i] = 0.f; }
+    if (e0 < D) {
+      load8(gamma, e0, gv[c]);
+      if (beta) load8(beta, e0, bv[c]);
+    }
+  }
+  const int64_t stride = (int64_t)gridDim.x * kRowsPerBlock;
+  for (int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave; row < T; row += stride) {
+    const E* arow = attn + row * D;
+    float a[NCH][8];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int e0 = (lane + 64 * c) * 8;
+      if (e0 < D) load8(arow, e0, a[c]);
+    }
+    float mu, rs;
+    row_stats<NCH>(a, lane, D, eps, mu, rs);
+    float m1 = 0.f, m2 = 0.f;
+    float dah[NCH][8];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int e0 = (lane + 64 * c) * 8;
+      if (e0 < D) {
+        float dyv[8], uv[8], duv[8];
+        load8(dy + row * D, e0, dyv);
+        load8(u + row * D, e0, uv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float ah = (a[c][i] - mu) * rs;
+          const float dn = dyv[i] * uv[i];
+          duv[i] = dyv[i] * (ah * gv[c][i] + bv[c][i]);
+          gsum[c][i] += dn * ah;
+          bsum[c][i] += dn;
+          dah[c][i] = dn * gv[c][i];
+          m1 += dah[c][i];
+          m2 += dah[c][i] * ah;
+          a[c][i] = ah;
+        }
+        store8(du + row * D, e0, duv);
+      }
+    }
+    m1 = wave_sum(m1) / (float)D;
+    m2 = wave_sum(m2) / (float)D;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int e0 = (lane + 64 * c) * 8;
+      if (e0 < D) {
+        float dav[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dav[i] = rs * (dah[c][i] - m1 - a[c][i] * m2);
+        store8(dattn + row * D, e0, dav);
+      }
+    }
+  }
+  // fixed-order combination of the 4 waves' column sums
+  for (int w = 0; w < kRowsPerBlock; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int e0 = (lane + 64 * c) * 8;
+        if (e0 < D)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            red[e0 + i] = (w == 0 ? 0.f : red[e0 + i]) + gsum[c][i];
+            red[D + e0 + i] = (w == 0 ? 0.f : red[D + e0 + i]) + bsum[c][i];
+          }
+      }
+    }
+    __syncthreads();
+  }
+  float* prow = partial + (int64_t)blockIdx.x * 2 * D;
+  for (int i = threadIdx.x; i < 2 * D; i += blockDim.x) prow[i] = red[i];
+}
+
+// dgamma[c] = sum over workgroups of partial[blk][0][c]; dbeta likewise from partial[blk][1][c]
+__global__ __launch_bounds__(256) void gated_norm_colsum_kernel(int nblk, int D, const float* __restrict__ partial,
+                                                                float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= 2 * D) return;
+  float s = 0.f;
+  for (int b = 0; b < nblk; ++b) s += partial[(int64_t)b * 2 * D + c];
+  if (c < D) dgamma[c] = s;
+  else if (dbeta) dbeta[c - D] = s;
+}
+
+int gated_norm_bwd_blocks(int64_t T) {
+  const int64_t need = (T + kRowsPerBlock - 1) / kRowsPerBlock;
+  return (int)(need < kMaxBwdBlocks ? need : kMaxBwdBlocks);
+}
+
+template <typename E, int NCH>
+static hipError_t fwd_one(int64_t T, int D, const void* attn, const void* u, const float* gamma, const float* beta,
+                          float eps, void* y, float* mean, float* rstd, hipStream_t stream) {
+  const unsigned grid = (unsigned)((T + kRowsPerBlock - 1) / kRowsPerBlock);
+  hipLaunchKernelGGL((gated_norm_fwd_kernel<E, NCH>), dim3(grid), dim3(64 * kRowsPerBlock), 0, stream, T, D,
+                     (const E*)attn, (const E*)u, gamma, beta, eps, (E*)y, mean, rstd);
+  return hipGetLastError();
+}
+
+template <typename E, int NCH>
+static hipError_t bwd_one(int64_t T, int D, const void* dy, const void* attn, const void* u, const float* gamma,
+                          const float* beta, float eps, void* dattn, void* du, float* dgamma, float* dbeta,
+                          float* partial, hipStream_t stream) {
+  const int nblk = gated_norm_bwd_blocks(T);
+  auto kern = gated_norm_bwd_kernel<E, NCH>;
+  const size_t smem = (size_t)2 * D * sizeof(float);
+  if (smem > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kern, dim3(nblk), dim3(64 * kRowsPerBlock), smem, stream, T, D, (const E*)dy, (const E*)attn,
+                     (const E*)u, gamma, beta, eps, (E*)dattn, (E*)du, partial);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(gated_norm_colsum_kernel, dim3((2 * D + 255) / 256), dim3(256), 0, stream, nblk, D, partial,
+                     dgamma, dbeta);
+  return hipGetLastError();
+}
+
+static int chunks_per_lane(int D) {
+  const int chunks = (D / 8 + 63) / 64;
+  int nch = 1;
+  while (nch < chunks) nch <<= 1;
+  return nch;
+}
+
+hipError_t launch_gated_norm_fwd(int64_t T, int D, int dtype, const void* attn, const void* u, const float* gamma,
+                                 const float* beta, float eps, void* y, float* mean, float* rstd, hipStream_t stream) {
+  const int nch = chunks_per_lane(D);
+#define FWD_CALL(E, N) fwd_one<E, N>(T, D, attn, u, gamma, beta, eps, y, mean, rstd, stream)
+  if (dtype == 0) {
+    switch (nch) {
+      case 1: return FWD_CALL(__bf16, 1);
+      case 2: return FWD_CALL(__bf16, 2);
+      case 4: return FWD_CALL(__bf16, 4);
+      case 8: return FWD_CALL(__bf16, 8);
+      default: return FWD_CALL(__bf16, 16);
+    }
+  }
+  switch (nch) {
+    case 1: return FWD_CALL(float, 1);
+    case 2: return FWD_CALL(float, 2);
+    case 4: return FWD_CALL(float, 4);
+    case 8: return FWD_CALL(float, 8);
+    default: return FWD_CALL(float, 16);
+  }
+#undef FWD_CALL
+}
+
+hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, const void* attn, const void* u,
+                                 const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
+                                 float* dbeta, float* partial, hipStream_t stream) {
+  const int nch = chunks_per_lane(D);
+#define BWD_CALL(E, N) bwd_one<E, N>(T, D, dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta, partial, stream)
+  if (dtype == 0) {
+    switch (nch) {
+      case 1: return BWD_CALL(__bf16, 1);
+      case 2: return BWD_CALL(__bf16, 2);
+      case 4: return BWD_CALL(__bf16, 4);
+      case 8: return BWD_CALL(__bf16, 8);
+      default: return BWD_CALL(__bf16, 16);
+    }
+  }
+  switch (nch) {
+    case 1: return BWD_CALL(float, 1);
+    case 2: return BWD_CALL(float, 2);
+    case 4: return BWD_CALL(float, 4);
+    case 8: return BWD_CALL(float, 8);
+    default: return BWD_CALL(float, 16);
+  }
+#undef BWD_CALL
+}
+
+}  // namespace hstu

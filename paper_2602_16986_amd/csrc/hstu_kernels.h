@@ -1,0 +1,63 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hstu {
+
+// First 256 bytes of every attention workspace.
+struct SchedHeader {
+  int32_t count;          // scheduled work items (row block x head)
+  int32_t pad;
+  int64_t tiles;          // scheduled (row block, column block) tiles, all heads
+  int64_t dense_tiles;    // tiles of the full L x L grids, all heads
+};
+
+struct WorkItem {
+  int32_t b;              // sequence
+  int32_t rb_h;           // (block index << 8) | head
+};
+
+// Everything a kernel needs to know about the attention problem.
+struct AttnArgs {
+  const void* q; const void* k; const void* v; const void* dout;
+  void* out; void* dq; void* dk; void* dv;
+  int64_t sq, sk, sv, so;           // row strides in elements
+  const int32_t* offsets;
+  const int32_t* num_targets;
+  int32_t B, H, D, T, max_seqlen;
+  int32_t K1, K2;
+  float alpha, inv_n;
+  const float* bias;                // expanded table [H, bias_stride] indexed by distance, or nullptr
+  int32_t bias_stride;
+  const SchedHeader* header;
+  const WorkItem* items;
+  int32_t max_items;
+};
+
+// schedule.hip
+// Builds the work list for blocks of `block_rows` rows (query rows in the forward and the dQ pass,
+// key rows when `key_major` is set) against column tiles of `tile_cols`.
+hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, bool key_major, SchedHeader* header,
+                           WorkItem* items, int32_t* seq_base, hipStream_t stream);
+hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
+                              hipStream_t stream);
+
+// attn_core.hip
+int fwd_block_rows(int dtype, int D);     // query rows per workgroup, forward
+int dq_block_rows(int dtype, int D);      // query rows per workgroup, dQ pass
+int dkv_block_rows(int dtype, int D);     // key rows per workgroup, dK/dV pass
+int stream_tile_rows(int dtype, int D);   // rows of one streamed LDS tile
+hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream);
+
+// gated_norm.hip
+int gated_norm_bwd_blocks(int64_t T);
+hipError_t launch_gated_norm_fwd(int64_t T, int D, int dtype, const void* attn, const void* u, const float* gamma,
+                                 const float* beta, float eps, void* y, float* mean, float* rstd, hipStream_t stream);
+hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, const void* attn, const void* u,
+                                 const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
+                                 float* dbeta, float* partial, hipStream_t stream);
+
+}  // namespace hstu

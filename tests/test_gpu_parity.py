@@ -1,0 +1,173 @@
+"""Parity of the HIP path (through the C ABI) against the CPU fp64 oracle, element by element,
+on the same seeded inputs.  Tolerances: max-abs error and max error normalised by the largest
+reference magnitude both <= 2e-2 for bf16 storage, <= 1e-5 for fp32."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hstu_oracle as orc
+from paper_2602_16986_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "fp32": 1e-5}
+
+
+@pytest.fixture(scope="module")
+def hb():
+    assert torch.cuda.is_available(), "GPU tests need a GPU; deselect with -m 'not gpu'"
+    from paper_2602_16986_amd import binding
+    return binding
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def check(name, got, ref, tol):
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    assert np.all(np.isfinite(got)), f"{name}: non-finite values"
+    err = np.abs(got - ref).max()
+    scale = np.abs(ref).max()
+    rel = err / scale if scale > 0 else err
+    print(f"  {name}: max_abs_err={err:.3e} max|ref|={scale:.3e} normalised={rel:.3e}", flush=True)
+    assert err <= tol, f"{name}: max abs error {err:.3e} > {tol}"
+    assert rel <= tol, f"{name}: normalised max error {rel:.3e} > {tol}"
+
+
+def oracle_args(w):
+    return dict(num_targets=w.num_targets, K1=w.K1, K2=w.K2, alpha=w.alpha, inv_n=1.0 / w.N, table=w.table,
+                bounds=w.bounds)
+
+
+def run_case(w, fused=False):
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    print(f"case {w.name}: lengths={w.lengths.tolist()} H={w.H} d={w.d} {w.dtype} K1={w.K1} K2={w.K2} "
+          f"targets={None if w.num_targets is None else w.num_targets.tolist()}", flush=True)
+    tol = TOL[w.dtype]
+    dw = DeviceWorkload(w, fused_qkvu=fused)
+    dw.out.fill_(float("nan"))
+    out = to_np(dw.attn_fwd())
+    torch.cuda.synchronize()
+    ref = orc.attn_fwd(w.q, w.k, w.v, w.offsets, **oracle_args(w))
+    check("A", out, ref, tol)
+    for t in (dw.dq, dw.dk, dw.dv):
+        t.fill_(float("nan"))
+    dq, dk, dv = (to_np(t) for t in dw.attn_bwd())
+    torch.cuda.synchronize()
+    rq, rk, rv = orc.attn_bwd(w.q, w.k, w.v, w.dout, w.offsets, **oracle_args(w))
+    check("dQ", dq, rq, tol)
+    check("dK", dk, rk, tol)
+    check("dV", dv, rv, tol)
+    return dw
+
+
+@pytest.mark.parametrize("name", wl.SMALL_CASES)
+def test_small_cases(hb, name):
+    run_case(wl.small(name))
+
+
+def test_config1_fp32_forward(hb):
+    w = wl.config("C1")
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    dw = DeviceWorkload(w)
+    out = to_np(dw.attn_fwd())
+    ref = orc.attn_fwd(w.q, w.k, w.v, w.offsets, **oracle_args(w))
+    check("A", out, ref, 1e-5)
+
+
+def test_fused_strided_views(hb):
+    # Q, K, V, U as column slices of one [T, 4*H*d] buffer: row strides differ from H*d
+    run_case(wl.small("bf16-sparse"), fused=True)
+
+
+def test_general_alpha(hb):
+    w = wl.small("bf16-targets-sparse")
+    w.alpha = 0.37
+    run_case(w)
+
+
+def test_empty_batch_and_errors(hb):
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.build("empty", [0, 0], 2, 128, "bf16", seed=0)
+    dw = DeviceWorkload(w)
+    dw.attn_fwd()
+    dw.attn_bwd()
+    torch.cuda.synchronize()
+    # too-small workspace and bad head_dim are reported, not launched
+    w2 = wl.small("bf16-dense")
+    dw2 = DeviceWorkload(w2)
+    with pytest.raises(hb.HstuError) as e:
+        hb.hstu_attn_fwd(dw2.problem, dw2.q, dw2.k, dw2.v, dw2.out, dw2.ws_fwd[:256])
+    assert e.value.status == -4
+    dw2.problem.params.head_dim = 48
+    with pytest.raises(hb.HstuError) as e:
+        hb.hstu_attn_fwd(dw2.problem, dw2.q, dw2.k, dw2.v, dw2.out, dw2.ws_fwd)
+    assert e.value.status == -3
+    dw2.problem.params.head_dim = 128
+    bad = w2.offsets.copy()
+    bad[2] = bad[1] - 1
+    dw2.problem._host[:] = bad
+    with pytest.raises(hb.HstuError) as e:
+        hb.hstu_attn_fwd(dw2.problem, dw2.q, dw2.k, dw2.v, dw2.out, dw2.ws_fwd)
+    assert e.value.status == -2
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 256), ("bf16", 1024), ("fp32", 64), ("bf16", 520), ("bf16", 4096)])
+def test_gated_norm(hb, dtype, D):
+    rng = np.random.default_rng(1)
+    T = 301
+    rnd = (lambda *s: wl.round_to_bf16(rng.standard_normal(s, dtype=np.float32))) if dtype == "bf16" else \
+          (lambda *s: rng.standard_normal(s, dtype=np.float32))
+    a, u, dy = rnd(T, D) * np.float32(0.01), rnd(T, D), rnd(T, D)
+    a = wl.round_to_bf16(a) if dtype == "bf16" else a
+    gamma = (1 + 0.1 * rng.standard_normal(D)).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(D)).astype(np.float32)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dev = "cuda:0"
+    ta, tu, tdy = (torch.from_numpy(x).to(dev, tdt) for x in (a, u, dy))
+    tg, tb = torch.from_numpy(gamma).to(dev), torch.from_numpy(beta).to(dev)
+    tol = TOL[dtype]
+    for use_beta in (False, True):
+        y = torch.full_like(ta, float("nan"))
+        mean = torch.empty(T, dtype=torch.float32, device=dev)
+        rstd = torch.empty(T, dtype=torch.float32, device=dev)
+        hb.hstu_gated_norm_fwd(ta, tu, tg, tb if use_beta else None, 1e-5, y, mean, rstd)
+        ry, rmean, rrstd = orc.gated_norm_fwd(a, u, gamma, beta if use_beta else None, 1e-5)
+        check(f"Y(beta={use_beta})", to_np(y), ry, tol)
+        check("mean", to_np(mean), rmean, 1e-5)
+        np.testing.assert_allclose(to_np(rstd), rrstd, rtol=1e-4)
+        da, du = torch.full_like(ta, float("nan")), torch.full_like(ta, float("nan"))
+        dg = torch.empty(D, dtype=torch.float32, device=dev)
+        db = torch.empty(D, dtype=torch.float32, device=dev)
+        ws = hb.new_workspace(hb.hstu_gated_norm_bwd_workspace_bytes(T, D), dev)
+        hb.hstu_gated_norm_bwd(tdy, ta, tu, tg, tb if use_beta else None, 1e-5, da, du, dg, db, ws)
+        rda, rdu, rdg, rdb = orc.gated_norm_bwd(dy, a, u, gamma, beta if use_beta else None, 1e-5)
+        check("dA", to_np(da), rda, tol)
+        check("dU", to_np(du), rdu, tol)
+        check("dgamma", to_np(dg), rdg, 1e-3 if dtype == "bf16" else 1e-5)
+        check("dbeta", to_np(db), rdb, 1e-3 if dtype == "bf16" else 1e-5)
+
+
+def test_layer_chain_small(hb):
+    """attention fwd -> gated norm fwd -> gated norm bwd -> attention bwd on one small batch,
+    each stage checked against the oracle fed with the GPU's own (rounded) input to that stage."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.small("bf16-targets")
+    dw = DeviceWorkload(w)
+    dw.layer_step()
+    torch.cuda.synchronize()
+    a_gpu = to_np(dw.out)
+    ry, _, _ = orc.gated_norm_fwd(a_gpu, w.u, w.gamma, None, w.eps)
+    check("Y", to_np(dw.y), ry, 2e-2)
+    rda, rdu, rdg, _ = orc.gated_norm_bwd(w.dy, a_gpu, w.u, w.gamma, None, w.eps)
+    check("dA", to_np(dw.dattn), rda, 2e-2)
+    check("dU", to_np(dw.du), rdu, 2e-2)
+    check("dgamma", to_np(dw.dgamma), rdg, 2e-2)
+    rq, rk, rv = orc.attn_bwd(w.q, w.k, w.v, to_np(dw.dattn), w.offsets, **oracle_args(w))
+    check("dQ", to_np(dw.dq), rq, 2e-2)
+    check("dK", to_np(dw.dk), rk, 2e-2)
+    check("dV", to_np(dw.dv), rv, 2e-2)
