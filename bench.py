@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the jagged HSTU attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3-dense]
+
+One step = one pass of the whole hot path over one synthetic jagged batch already resident in HBM:
+tile scheduling + bias expansion + attention forward, gated-norm forward, gated-norm backward,
+attention backward (dQ pass and dK/dV pass).  Prints ONE JSON line.  `value` is useful attention
+TFLOP/s (forward 4*d + backward 10*d FLOPs per unmasked pair and head) over the whole step time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3-dense",
+                    help="C1, C2, C3-dense, C3-sparse, C4, C5 (default: the 8k-16k config the metric is quoted on)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fwd-only", action="store_true", help="time the forward attention only (profiling aid)")
+    return ap.parse_args()
+
+
+def time_loop(fn, steps, torch):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline(w, fl, target_seconds):
+    """The oracle as it stands, timed on this host's cores on a bounded row sample of the same batch."""
+    from oracle import hstu_oracle as orc
+    rng = np.random.default_rng(123)
+    kw = dict(num_targets=w.num_targets, K1=w.K1, K2=w.K2, alpha=w.alpha, inv_n=1.0 / w.N, table=w.table,
+              bounds=w.bounds)
+    threads = orc.num_threads()
+    # pilot on a few rows to size the sample
+    pilot = np.sort(rng.choice(w.T, size=min(w.T, 8 * threads), replace=False))
+    q, k, v, do = (x.astype(np.float64) for x in (w.q, w.k, w.v, w.dout))
+    t0 = time.time()
+    orc.attn_fwd(q, k, v, w.offsets, rows=pilot, **kw)
+    if w.backward:
+        orc.attn_bwd(q, k, v, do, w.offsets, rows=pilot, **kw)
+    per_row = (time.time() - t0) / len(pilot)
+    n = int(max(len(pilot), min(w.T, target_seconds / max(per_row, 1e-9))))
+    rows = np.sort(rng.choice(w.T, size=n, replace=False))
+    t0 = time.time()
+    orc.attn_fwd(q, k, v, w.offsets, rows=rows, **kw)
+    if w.backward:
+        orc.attn_bwd(q, k, v, do, w.offsets, rows=rows, **kw)
+    dt = time.time() - t0
+    flops_total = fl["fwd"] + (fl["bwd"] if w.backward else 0.0)
+    # a uniform row sample carries the same fraction of the pairs in expectation
+    sample_flops = flops_total * n / w.T
+    return {"value": sample_flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} of {w.T} token rows drawn uniformly (all heads): oracle forward"
+                      f"{' + backward (dQ, dK, dV rows)' if w.backward else ''}, fp64, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (sequences shard across GPUs "
+              "with no exchange in the attention path, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2602_16986_amd import binding as hb
+    from paper_2602_16986_amd import flops, workloads
+    from paper_2602_16986_amd.runner import DeviceWorkload
+
+    w = workloads.config(args.workload)
+    fl = flops.attention_flops(w)
+    dw = DeviceWorkload(w)
+    do_bwd = w.backward and not args.fwd_only
+
+    def step():
+        if do_bwd:
+            dw.layer_step()
+        else:
+            dw.attn_fwd()
+
+    for _ in range(args.warmup):
+        step()
+    ms_step = time_loop(step, args.steps, torch)
+
+    # per-entry-point and per-kernel times (separate loops, HIP events inside the library)
+    parts = {"attn_fwd": time_loop(dw.attn_fwd, args.steps, torch)}
+    if do_bwd:
+        parts["gated_norm_fwd"] = time_loop(dw.norm_fwd, args.steps, torch)
+        parts["gated_norm_bwd"] = time_loop(dw.norm_bwd, args.steps, torch)
+        parts["attn_bwd"] = time_loop(lambda: dw.attn_bwd(dout=dw.dattn), args.steps, torch)
+    hb.hstu_profile_enable(True)
+    kern = {}
+    for _ in range(args.steps):
+        step()
+        for name, ms in hb.hstu_profile_read():
+            kern.setdefault(name, []).append(ms)
+    hb.hstu_profile_enable(False)
+    kern = {k: float(np.mean(v)) for k, v in kern.items()}
+
+    useful = fl["fwd"] + (fl["bwd"] if do_bwd else 0.0)
+    value = useful / (ms_step * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
+
+    # roofline of the dominant kernel.  Algorithmic FLOPs per launch = products the kernel owes per
+    # unmasked pair: forward 2 (4d), dQ pass 3 (6d: S, dP, dQ), dK/dV pass 4 (8d: S, dP, dK, dV).
+    algo = {"attn_fwd": 4.0, "attn_bwd_dq": 6.0, "attn_bwd_dkdv": 8.0}
+    dom = max((k for k in kern if k in algo), key=lambda k: kern[k])
+    achieved = algo[dom] * w.d * fl["pairs"] / (kern[dom] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                "frac": achieved / peak, "traffic": None}
+
+    sched = hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)
+    eb = flops.epilogue_bytes(w)
+    out = {
+        "metric": "useful TFLOP/s (fwd, fwd+bwd) & % bf16 MFMA peak, jagged HSTU attention",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "pass": "fwd+bwd+epilogue" if do_bwd else "fwd", "B": w.B, "T": w.T, "H": w.H,
+                   "d": w.d, "K1": w.K1, "K2": w.K2, "min_len": int(w.lengths.min()), "max_len": int(w.lengths.max()),
+                   "unmasked_pairs": fl["pairs"]},
+        "frac_of_peak": value / peak,
+        "fwd_tflops": fl["fwd"] / (kern["attn_fwd"] * 1e-3) / 1e12,
+        "fwd_frac_of_peak": fl["fwd"] / (kern["attn_fwd"] * 1e-3) / 1e12 / peak,
+        "roofline": roofline,
+        "entry_ms": parts, "kernel_ms": kern,
+        "schedule": {**sched, "skipped_tile_frac": 1.0 - sched["tiles"] / max(sched["dense_tiles"], 1)},
+    }
+    if do_bwd:
+        bwd_ms = kern["attn_bwd_dq"] + kern["attn_bwd_dkdv"]
+        out["bwd_tflops"] = fl["bwd"] / (bwd_ms * 1e-3) / 1e12
+        out["bwd_tflops_strict"] = fl["bwd_strict"] / (bwd_ms * 1e-3) / 1e12
+        out["bwd_frac_of_peak"] = out["bwd_tflops"] / peak
+        out["epilogue_gbs"] = {"fwd": eb["fwd"] / (kern["gated_norm_fwd"] * 1e-3) / 1e9,
+                               "bwd": eb["bwd"] / (kern["gated_norm_bwd"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, fl, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

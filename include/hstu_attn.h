@@ -129,6 +129,15 @@ const char* hstu_status_string(int status);
  * grid would have.  Reads device memory with a blocking copy; for reporting only. */
 int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, int for_backward, int64_t out[3]);
 
+/* Per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every kernel
+ * launch made by the entry points above is bracketed by HIP events on its stream (up to 16 launches
+ * between two reads).  hstu_profile_read waits for those events and returns the number of entries
+ * written: names[i] (static strings: "attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "gated_norm_fwd",
+ * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_*", "bias_expand") and
+ * ms[i] = elapsed milliseconds.  HOST arrays.  Not thread-safe; enable(1) creates the events once. */
+int hstu_profile_enable(int on);
+int hstu_profile_read(int max_entries, const char** names, float* ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -62,13 +62,17 @@ def _load() -> ctypes.CDLL:
     lib.hstu_gated_norm_bwd_workspace_bytes.argtypes = [i64, i32]
     lib.hstu_gated_norm_bwd.restype = ctypes.c_int
     lib.hstu_gated_norm_bwd.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.hstu_profile_enable.restype = ctypes.c_int
+    lib.hstu_profile_enable.argtypes = [ctypes.c_int]
+    lib.hstu_profile_read.restype = ctypes.c_int
+    lib.hstu_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float)]
     return lib
 
 
 _lib = _load()
 EXPORTS = ["hstu_attn_workspace_bytes", "hstu_attn_fwd", "hstu_attn_bwd", "hstu_gated_norm_fwd",
            "hstu_gated_norm_bwd_workspace_bytes", "hstu_gated_norm_bwd", "hstu_status_string",
-           "hstu_attn_schedule_stats"]
+           "hstu_attn_schedule_stats", "hstu_profile_enable", "hstu_profile_read"]
 
 
 def status_string(status: int) -> str:
@@ -106,7 +110,7 @@ class AttnProblem:
         p.num_heads, p.head_dim, p.total_tokens, p.max_seqlen = H, d, T, int(max_seqlen)
         p.dtype = _dtype_code(q)
         for name, t in (("q", q), ("k", k), ("v", v), ("o", out_like)):
-            assert t.stride(2) == 1 and t.stride(1) == d, "head stride must be d, features contiguous"
+            assert T == 0 or (t.stride(2) == 1 and t.stride(1) == d), "head stride must be d, features contiguous"
             setattr(p, f"row_stride_{name}", t.stride(0) if T > 0 else H * d)
         p.seq_offsets = _ptr(seq_offsets)
         p.seq_offsets_host = None if self._host is None else self._host.ctypes.data
@@ -172,3 +176,19 @@ def hstu_gated_norm_bwd(dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta,
                                   workspace.numel(), _stream(stream))
     if st != HSTU_OK:
         raise HstuError(st, "hstu_gated_norm_bwd")
+
+
+def hstu_profile_enable(on: bool) -> None:
+    st = _lib.hstu_profile_enable(1 if on else 0)
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_profile_enable")
+
+
+def hstu_profile_read(max_entries: int = 16):
+    """[(kernel name, milliseconds)] for the launches since the last read; waits for them to finish."""
+    names = (ctypes.c_char_p * max_entries)()
+    ms = (ctypes.c_float * max_entries)()
+    n = _lib.hstu_profile_read(max_entries, names, ms)
+    if n < 0:
+        raise HstuError(n, "hstu_profile_read")
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]

@@ -91,9 +91,58 @@ hipError_t prepare_bias(const hstu_attn_params* p, AttnArgs& a, unsigned char* w
   return launch_bias_expand(p->rab_table, p->rab_bounds, p->num_buckets, p->num_heads, a.bias_stride, bias, stream);
 }
 
+// ---- optional per-kernel timing (for benchmarks): HIP events around every launch, on the launch stream
+constexpr int kProfSlots = 16;
+struct ProfSlot { const char* name; hipEvent_t e0, e1; bool used; };
+ProfSlot g_prof[kProfSlots];
+bool g_prof_on = false, g_prof_init = false;
+int g_prof_n = 0;
+
+struct ProfScope {
+  ProfSlot* s;
+  hipStream_t stream;
+  ProfScope(const char* name, hipStream_t st) : s(nullptr), stream(st) {
+    if (!g_prof_on || g_prof_n >= kProfSlots) return;
+    s = &g_prof[g_prof_n++];
+    s->name = name;
+    s->used = hipEventRecord(s->e0, stream) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (s && s->used) s->used = hipEventRecord(s->e1, stream) == hipSuccess;
+  }
+};
+
 }  // namespace
 
 extern "C" {
+
+int hstu_profile_enable(int on) {
+  if (on && !g_prof_init) {
+    for (int i = 0; i < kProfSlots; ++i) {
+      if (hipEventCreate(&g_prof[i].e0) != hipSuccess || hipEventCreate(&g_prof[i].e1) != hipSuccess) return HSTU_ERR_LAUNCH;
+      g_prof[i].used = false;
+    }
+    g_prof_init = true;
+  }
+  g_prof_on = on != 0;
+  g_prof_n = 0;
+  return HSTU_OK;
+}
+
+int hstu_profile_read(int max_entries, const char** names, float* ms) {
+  int n = 0;
+  for (int i = 0; i < g_prof_n && n < max_entries; ++i) {
+    if (!g_prof[i].used) continue;
+    if (hipEventSynchronize(g_prof[i].e1) != hipSuccess) return HSTU_ERR_LAUNCH;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_prof[i].e0, g_prof[i].e1) != hipSuccess) return HSTU_ERR_LAUNCH;
+    names[n] = g_prof[i].name;
+    ms[n] = t;
+    ++n;
+  }
+  g_prof_n = 0;
+  return n;
+}
 
 const char* hstu_status_string(int status) {
   switch (status) {
@@ -129,12 +178,21 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
   a.max_items = l.max_items[0];
   a.header = (const SchedHeader*)(ws + l.header[0]);
   a.items = (const WorkItem*)(ws + l.items[0]);
-  if (launch_schedule(a, fwd_block_rows(p->dtype, p->head_dim), stream_tile_rows(p->dtype, p->head_dim), false,
-                      (SchedHeader*)(ws + l.header[0]), (WorkItem*)(ws + l.items[0]), (int32_t*)(ws + l.seq_base[0]),
-                      stream) != hipSuccess)
-    return HSTU_ERR_LAUNCH;
-  if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
-  if (launch_attn_fwd(a, p->dtype, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  {
+    ProfScope ps("schedule_fwd", stream);
+    if (launch_schedule(a, fwd_block_rows(p->dtype, p->head_dim), stream_tile_rows(p->dtype, p->head_dim), false,
+                        (SchedHeader*)(ws + l.header[0]), (WorkItem*)(ws + l.items[0]), (int32_t*)(ws + l.seq_base[0]),
+                        stream) != hipSuccess)
+      return HSTU_ERR_LAUNCH;
+  }
+  {
+    ProfScope ps("bias_expand", stream);
+    if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  }
+  {
+    ProfScope ps("attn_fwd", stream);
+    if (launch_attn_fwd(a, p->dtype, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  }
   return HSTU_OK;
 }
 
@@ -155,15 +213,22 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
   AttnArgs a = make_args(p, q, k, v);
   a.dout = dout; a.dq = dq; a.dk = dk; a.dv = dv;
   const int tile = stream_tile_rows(p->dtype, p->head_dim);
-  if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  {
+    ProfScope ps("bias_expand", stream);
+    if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  }
   for (int s = 0; s < 2; ++s) {                          // s = 0: dQ pass (query blocks), s = 1: dK/dV pass (key blocks)
     a.max_items = l.max_items[s];
     a.header = (const SchedHeader*)(ws + l.header[s]);
     a.items = (const WorkItem*)(ws + l.items[s]);
     const int rows = s == 0 ? dq_block_rows(p->dtype, p->head_dim) : dkv_block_rows(p->dtype, p->head_dim);
-    if (launch_schedule(a, rows, tile, s == 1, (SchedHeader*)(ws + l.header[s]), (WorkItem*)(ws + l.items[s]),
-                        (int32_t*)(ws + l.seq_base[s]), stream) != hipSuccess)
-      return HSTU_ERR_LAUNCH;
+    {
+      ProfScope ps(s == 0 ? "schedule_dq" : "schedule_dkdv", stream);
+      if (launch_schedule(a, rows, tile, s == 1, (SchedHeader*)(ws + l.header[s]), (WorkItem*)(ws + l.items[s]),
+                          (int32_t*)(ws + l.seq_base[s]), stream) != hipSuccess)
+        return HSTU_ERR_LAUNCH;
+    }
+    ProfScope ps(s == 0 ? "attn_bwd_dq" : "attn_bwd_dkdv", stream);
     const hipError_t e = s == 0 ? launch_attn_bwd_dq(a, p->dtype, stream) : launch_attn_bwd_dkdv(a, p->dtype, stream);
     if (e != hipSuccess) return HSTU_ERR_LAUNCH;
   }
@@ -196,6 +261,7 @@ int hstu_gated_norm_fwd(int64_t T, int32_t D, int32_t dtype, const void* attn, c
   if (T == 0) return HSTU_OK;
   if (!attn || !u || !gamma || !y) return HSTU_ERR_NULL;
   if (misaligned(attn) || misaligned(u) || misaligned(gamma) || misaligned(y) || (beta && misaligned(beta))) return HSTU_ERR_SHAPE;
+  ProfScope ps("gated_norm_fwd", (hipStream_t)stream);
   if (launch_gated_norm_fwd(T, D, dtype, attn, u, gamma, beta, eps, y, mean, rstd, (hipStream_t)stream) != hipSuccess)
     return HSTU_ERR_LAUNCH;
   return HSTU_OK;
@@ -219,6 +285,7 @@ int hstu_gated_norm_bwd(int64_t T, int32_t D, int32_t dtype, const void* dy, con
     return HSTU_ERR_SHAPE;
   if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < hstu_gated_norm_bwd_workspace_bytes(T, D))
     return HSTU_ERR_WORKSPACE;
+  ProfScope ps("gated_norm_bwd", (hipStream_t)stream);
   if (launch_gated_norm_bwd(T, D, dtype, dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta, (float*)workspace,
                             (hipStream_t)stream) != hipSuccess)
     return HSTU_ERR_LAUNCH;

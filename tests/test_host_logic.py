@@ -64,3 +64,18 @@ def test_library_exports_every_declared_symbol():
     lib.hstu_status_string.restype = ctypes.c_char_p
     assert lib.hstu_status_string(0) == b"HSTU_OK"
     assert b"WORKSPACE" in lib.hstu_status_string(-4)
+
+
+def test_flop_accounting_matches_oracle_pair_count():
+    from oracle import hstu_oracle as orc
+    from paper_2602_16986_amd import flops
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        L = int(rng.integers(0, 300))
+        M = int(rng.integers(0, L + 1)) if rng.random() < 0.5 else 0
+        K1 = int(rng.choice([-1, 0, 1, 2, 17, 64, 1000]))
+        K2 = int(rng.choice([0, 1, 9, 64, 1000]))
+        assert flops.visible_pairs_one(L, M, K1, K2) == orc.count_pairs([L], [M], K1, K2), (L, M, K1, K2)
+    from paper_2602_16986_amd import workloads as wl
+    w = wl.config("C1")
+    assert flops.attention_flops(w)["pairs"] == 62278
