@@ -14,7 +14,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhstu_attn.so")
+# HSTU_ATTN_LIB lets a developer point the binding at another build of the same library
+LIB_PATH = os.environ.get("HSTU_ATTN_LIB") or os.path.join(_HERE, "libhstu_attn.so")
 
 HSTU_BF16, HSTU_FP32 = 0, 1
 HSTU_OK = 0

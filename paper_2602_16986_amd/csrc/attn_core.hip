@@ -21,6 +21,8 @@
 // wants for its B operand, so P / dS never travel through LDS; the streamed tile is read
 // once more through the LDS transpose loads (ds_read_b64_tr_b16) to form the A operand of
 // the second product.  The fp32 instantiation uses v_mfma_f32_32x32x2_f32 the same way.
+#include <type_traits>
+
 #include "hstu_common.h"
 #include "hstu_kernels.h"
 
@@ -35,8 +37,23 @@ struct Cfg {
   static constexpr int BN = kBf16 ? 64 : 32;                    // streamed rows per LDS tile
   static constexpr int NT = 64 * NWAVES;
   static constexpr int ROW_BYTES = D * (int)sizeof(E);
-  static constexpr int STRIDE = ROW_BYTES + (kBf16 ? 80 : 16);  // LDS row stride, bytes
-  static constexpr int TILE_BYTES = BN * STRIDE;
+  // LDS tiles are read two ways: 16-byte reads with one streamed row per lane (score products)
+  // and transpose reads that touch 4 consecutive rows x 64 bytes per 32 lanes (second products).
+  // A tile read only one way gets the row padding that makes that way conflict-free (16 bytes
+  // for row-per-lane reads, 64 for transpose reads) and plain base+offset addressing.  For 256-byte
+  // bf16 rows no padding serves both ways, so a tile read both ways is unpadded and stores the
+  // 16-byte chunks of row r at chunk ^ swz(r), swz(r) = 4*(r%4) + (r/4)%4: 16 consecutive rows then
+  // map one logical chunk to 16 different bank groups, and 4 consecutive rows map 4 consecutive
+  // chunks to 16 different ones.
+  //   tensor 0 (Y1): K in the forward (rows only), K in the dQ pass and Q in the dK/dV pass (both ways)
+  //   tensor 1 (Y2): V in the forward (transposed only), V in the dQ pass (rows only), dO in dK/dV (both)
+  static constexpr bool kBoth0 = MODE != kFwd, kBoth1 = MODE == kBwdDKDV;
+  static constexpr bool kSwz0 = kBf16 && D == 128 && kBoth0, kSwz1 = kBf16 && D == 128 && kBoth1;
+  static constexpr int PAD0 = !kBf16 ? 16 : (kSwz0 ? 0 : (kBoth0 ? 80 : 16));
+  static constexpr int PAD1 = !kBf16 ? 16 : (kSwz1 ? 0 : (kBoth1 ? 80 : (MODE == kFwd ? 64 : 16)));
+  static constexpr int STRIDE0 = ROW_BYTES + PAD0, STRIDE1 = ROW_BYTES + PAD1;   // LDS row strides, bytes
+  static constexpr int TILE0 = BN * STRIDE0, TILE1 = BN * STRIDE1;
+  static constexpr int STAGE_BYTES = TILE0 + TILE1;
   static constexpr int CPR = ROW_BYTES / 16;                    // 16-byte chunks per row
   static constexpr int CHUNKS = BN * CPR;
   static constexpr int CPT = (CHUNKS + NT - 1) / NT;            // chunks per thread per tensor
@@ -44,12 +61,27 @@ struct Cfg {
   static constexpr int NOUT = (MODE == kBwdDKDV) ? 2 : 1;       // output accumulators
   static constexpr int KS = kBf16 ? D / 16 : D / 2;             // k-steps of a score product
   static constexpr int OB = D / 32;                             // 32-feature output blocks
-  static constexpr int SMEM_BYTES = 4 * TILE_BYTES;             // 2 stages x 2 tensors
+  // Relative-bias strip of one (block, tile): the bias depends on i - j only, so a tile needs
+  // BX + BN - 1 consecutive table entries.  Four copies shifted by 0..3 entries let every lane
+  // fetch 4 consecutive entries with one aligned 16-byte LDS read.
+  // Copy length = 16 (mod 64) entries keeps the 16 reads of a quarter-wave on 16 different bank groups.
+  static constexpr int SLEN = (BX + BN + 4 - 16 + 63) / 64 * 64 + 16;   // entries per copy
+  static constexpr int STRIP_BYTES = 4 * SLEN * 4;
+  static constexpr int STRIP_BASE = 2 * STAGE_BYTES;
+  static constexpr int SMEM_BYTES = 2 * STAGE_BYTES + 2 * STRIP_BYTES;  // 2 stages x (2 tensors + strip)
 };
 
 template <typename E> struct ResidentFrag;
 template <> struct ResidentFrag<__bf16> { typedef bf16x8 type; };
 template <> struct ResidentFrag<float> { typedef float type; };
+
+// byte offset of logical 16-byte chunk `chunk` of tile row `row`
+template <typename C, int TENSOR>
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+  constexpr int stride = TENSOR == 0 ? C::STRIDE0 : C::STRIDE1;
+  if constexpr (TENSOR == 0 ? C::kSwz0 : C::kSwz1) return row * stride + ((chunk ^ (4 * (row & 3) + ((row >> 2) & 3))) << 4);
+  else return row * stride + (chunk << 4);
+}
 
 __device__ __forceinline__ float sigmoid_fast(float s) {
   const float e = __builtin_amdgcn_exp2f(s * -1.4426950408889634f);
@@ -74,7 +106,8 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
   const int L = a.offsets[b + 1] - seq0;
   const SeqGeom g = {L, L - (a.num_targets ? a.num_targets[b] : 0), a.K1, a.K2};
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // scalar: per-wave decisions stay on the SALU
   const int hf = lane >> 5, l32 = lane & 31, grp16 = lane >> 4, i16 = lane & 15;
   const int x0 = xb * C::BX;
   const int xw0 = x0 + wave * 32;
@@ -114,6 +147,13 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
     }
   }
 
+  // The resident operands must have landed before the tile loop: inside it the only global loads
+  // in flight are the next tile's, and nothing may force a wait on those before they are needed.
+#pragma unroll
+  for (int i = 0; i < C::NRES; ++i)
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+v"(res[i][ks]));
+
   f32x16 out[C::NOUT][C::OB];
 #pragma unroll
   for (int o = 0; o < C::NOUT; ++o)
@@ -127,31 +167,48 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
   const int ntiles = tr.count();
   const float* bias_h = a.bias ? a.bias + (int64_t)h * a.bias_stride : nullptr;
   const bool unit_alpha = a.alpha == 1.0f;
+  // this lane's start inside the bias strip: copy c = s0 mod 4 makes its 4-entry reads 16-byte aligned
+  const int strip_s0 = C::BX - 1 - (wave * 32 + l32) + 4 * hf;
+  const int strip_lane = (strip_s0 & 3) * C::SLEN + (strip_s0 & ~3);
 
   // ---- global -> register -> LDS staging of the streamed tiles
   u32x4 pre1[C::CPT], pre2[C::CPT];
+  float pre_bias = 0.f;
+  // strip[s] = bias(distance) for s = (y - tile start) + (BX - 1 - (x - x0)); the distance grows with
+  // x - y in the query-stationary passes and with y - x in the key-stationary pass
   auto gload = [&](int yt) {
+    if (bias_h) {
+      const int base = (MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) + tid : x0 + (C::BX - 1) - yt * C::BN - tid;
+      pre_bias = 0.f;
+      if (tid < C::BX + C::BN - 1 && base >= 0 && base < a.bias_stride) pre_bias = bias_h[base];
+    }
 #pragma unroll
     for (int c = 0; c < C::CPT; ++c) {
       const int idx = tid + c * C::NT;
       const int row = idx / C::CPR, col = idx % C::CPR;
-      const int y = yt * C::BN + row;
-      pre1[c] = (u32x4){0u, 0u, 0u, 0u};
-      pre2[c] = (u32x4){0u, 0u, 0u, 0u};
-      if (idx < C::CHUNKS && y < L) {                                    // rows past the sequence end read as zero
+      // rows past the sequence end re-read its last row: finite data, and every pair that involves
+      // them is masked (their coefficient is exactly zero)
+      const int y = min(yt * C::BN + row, L - 1);
+      if (C::CHUNKS % C::NT == 0 || idx < C::CHUNKS) {
         pre1[c] = *(const u32x4*)((const unsigned char*)(Y1 + (int64_t)y * sy1) + col * 16);
         pre2[c] = *(const u32x4*)((const unsigned char*)(Y2 + (int64_t)y * sy2) + col * 16);
       }
     }
   };
   auto lstore = [&](int stage) {
+    if (bias_h && tid < C::BX + C::BN - 1) {
+      float* strip = (float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES);
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (tid - c >= 0) strip[c * C::SLEN + tid - c] = pre_bias;        // copy c holds strip[m + c] at m
+    }
 #pragma unroll
     for (int c = 0; c < C::CPT; ++c) {
       const int idx = tid + c * C::NT;
       const int row = idx / C::CPR, col = idx % C::CPR;
-      if (idx < C::CHUNKS) {
-        *(u32x4*)(smem + (stage * 2 + 0) * C::TILE_BYTES + row * C::STRIDE + col * 16) = pre1[c];
-        *(u32x4*)(smem + (stage * 2 + 1) * C::TILE_BYTES + row * C::STRIDE + col * 16) = pre2[c];
+      if (C::CHUNKS % C::NT == 0 || idx < C::CHUNKS) {
+        *(u32x4*)(smem + stage * C::STAGE_BYTES + lds_off<C, 0>(row, col)) = pre1[c];
+        *(u32x4*)(smem + stage * C::STAGE_BYTES + C::TILE0 + lds_off<C, 1>(row, col)) = pre2[c];
       }
     }
   };
@@ -162,136 +219,275 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
   }
   __syncthreads();
 
+  constexpr int NSB = C::BN / 32;                     // 32-row sub-blocks of a streamed tile
+  constexpr int SBG = (MODE == kFwd && NSB >= 2) ? 2 : 1;   // sub-blocks whose products are interleaved
   for (int t = 0; t < ntiles; ++t) {
     const int yt = tr.at(t);
     const int stage = t & 1;
     if (t + 1 < ntiles) gload(tr.at(t + 1));
-    const unsigned char* y1s = smem + (stage * 2 + 0) * C::TILE_BYTES;
-    const unsigned char* y2s = smem + (stage * 2 + 1) * C::TILE_BYTES;
+    const unsigned char* y1s = smem + stage * C::STAGE_BYTES;
+    const unsigned char* y2s = y1s + C::TILE0;
+    const int y0 = yt * C::BN;
 
-#pragma unroll
-    for (int sb = 0; sb < C::BN / 32; ++sb) {
-      const int ys0 = yt * C::BN + sb * 32;
-      int kind = (MODE == kBwdDKDV) ? classify_tile(g, ys0, ys0 + 31, xw0, xw0 + 31)
-                                    : classify_tile(g, xw0, xw0 + 31, ys0, ys0 + 31);
-      if (xw0 >= L) kind = kTileEmpty;
-      if (kind == kTileEmpty) continue;                                  // wave-uniform
-      if (kind == kTileFull && !unit_alpha) kind = kTilePartial;         // general alpha: generic path
+    // How this wave's 32 stationary rows relate to the tile: nothing visible (skip), everything
+    // visible (no mask arithmetic, bias from the strip), or mixed (generic per-element path).
+    int kind = (MODE == kBwdDKDV) ? classify_tile(g, y0, y0 + C::BN - 1, xw0, xw0 + 31)
+                                  : classify_tile(g, xw0, xw0 + 31, y0, y0 + C::BN - 1);
+    if (xw0 >= L) kind = kTileEmpty;
+    if (kind == kTileFull && !unit_alpha) kind = kTilePartial;           // general alpha: generic path
 
-      // ---- scores
-      f32x16 sc1, sc2;
+    bool done = false;
+    if constexpr (MODE == kFwd && C::kBf16 && NSB == 2 && D == 128) {
+      if (kind == kTileFull) {
+        // Software-pipelined forward for fully visible tiles.  The SiLU of one 32-key sub-block is
+        // issued between the matrix instructions of the next product, so the matrix pipe and the
+        // vector ALU of this wave work at the same time:
+        //   S(0) | S(1) + SiLU(0) | PV(0) + SiLU(1) | PV(1)
+        typedef __attribute__((address_space(3))) short4v* lds_s4;
+        const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
+        const unsigned char* krow = y1s + l32 * C::STRIDE0 + hf * 16;                 // + sb*32*STRIDE0 + ks*32
+        const unsigned char* vtr = y2s + (4 * hf + (i16 >> 2)) * C::STRIDE1 + (2 * (grp16 & 1) + ((i16 & 3) >> 1)) * 16 + 8 * (i16 & 1);
+        auto seed = [&](int sb, f32x16& acc) {
+          if (bias_h) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sc1[r] = 0.f; sc2[r] = 0.f; }
-      if (kind == kTileFull && bias_h) {
-        // every pair is visible and i - j >= 0: seed the accumulator with the bias
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int y = ys0 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          sc1[r] = bias_h[(MODE == kBwdDKDV) ? y - x : x - y];
-        }
-      }
-      const unsigned char* y1row = y1s + (sb * 32 + l32) * C::STRIDE;
-      const unsigned char* y2row = y2s + (sb * 32 + l32) * C::STRIDE;
-#pragma unroll
-      for (int ks = 0; ks < C::KS; ++ks) {
-        if constexpr (C::kBf16) {
-          const bf16x8 af = *(const bf16x8*)(y1row + (ks * 16 + hf * 8) * 2);
-          sc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, res[0][ks], sc1, 0, 0, 0);
-        } else {
-          const float af = *(const float*)(y1row + (2 * ks + hf) * 4);
-          sc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(af, res[0][ks], sc1, 0, 0, 0);
-        }
-      }
-      if constexpr (MODE != kFwd) {
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-          if constexpr (C::kBf16) {
-            const bf16x8 af = *(const bf16x8*)(y2row + (ks * 16 + hf * 8) * 2);
-            sc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, res[1][ks], sc2, 0, 0, 0);
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const f32x4 bv = *(const f32x4*)(strip + sb * 32 + 8 * q4);
+              acc[4 * q4 + 0] = bv[0]; acc[4 * q4 + 1] = bv[1]; acc[4 * q4 + 2] = bv[2]; acc[4 * q4 + 3] = bv[3];
+            }
           } else {
-            const float af = *(const float*)(y2row + (2 * ks + hf) * 4);
-            sc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(af, res[1][ks], sc2, 0, 0, 0);
-          }
-        }
-      }
-
-      // ---- pointwise: SiLU (forward) or its derivative times dP (backward), mask in registers
-      float c1[16], c2[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float s = sc1[r];
-        bool vis = true;
-        if (kind == kTilePartial) {
-          const int y = ys0 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          int delta;
-          vis = (MODE == kBwdDKDV) ? visible(g, y, x, delta) : visible(g, x, y, delta);
-          float bv = 0.f;
-          if (bias_h && vis) bv = bias_h[delta];
-          s = fmaf(s, a.alpha, bv);
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+          }
+        };
+        auto kfrag = [&](int sb, int ks) -> bf16x8 { return *(const bf16x8*)(krow + sb * 32 * C::STRIDE0 + ks * 32); };
+        auto vfrag = [&](int sb, int step) -> bf16x8 {           // step = ks2 * OB + ob
+          const int ks2 = step / C::OB, ob = step % C::OB;
+          const unsigned char* ptr = vtr + (sb * 32 + ks2 * 16) * C::STRIDE1 + ob * 64;
+          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)ptr);
+          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(ptr + 8 * C::STRIDE1));
+          return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
+        auto silu2 = [&](const f32x16& sc, int m) -> uint32_t {   // elements 2m, 2m+1 -> packed bf16 pair
+          const float s0v = sc[2 * m], s1v = sc[2 * m + 1];
+          return pack_bf16x2(s0v * sigmoid_fast(s0v), s1v * sigmoid_fast(s1v));
+        };
+        // LDS fragments are fetched PF products ahead of their use: the latency of an LDS read is
+        // several matrix instructions long
+        constexpr int PF = 4;
+        f32x16 s0, s1;
+        uint32_t p0[8], p1[8];
+        bf16x8 kf[PF];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) kf[i] = kfrag(0, i);
+        seed(0, s0);
+        seed(1, s1);
+        // S(0): k-steps 0..7 of sub-block 0, then S(1) + SiLU(0); fragment index n = sb*8 + ks
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {
+          const bf16x8 fa = kf[n % PF];
+          if (n + PF < 16) kf[n % PF] = kfrag((n + PF) / 8, (n + PF) % 8);
+          __builtin_amdgcn_sched_barrier(0);
+          if (n < 8) {
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, res[0][n], s0, 0, 0, 0);
+          } else {
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, res[0][n - 8], s1, 0, 0, 0);
+            p0[n - 8] = silu2(s0, n - 8);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
-        const float sig = sigmoid_fast(s);
-        const float p = s * sig;
-        if (MODE == kFwd) {
-          c1[r] = vis ? p : 0.f;
+        // PV(0) + SiLU(1), then PV(1); fragment index n = sb*8 + ks2*OB + ob
+        bf16x8 vf[PF];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) vf[i] = vfrag(0, i);
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {
+          const bf16x8 va = vf[n % PF];
+          if (n + PF < 16) vf[n % PF] = vfrag((n + PF) / 8, (n + PF) % 8);
+          __builtin_amdgcn_sched_barrier(0);
+          const int step = n % 8, ks2 = step / C::OB, ob = step % C::OB;
+          if (n < 8) {
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){p0[4 * ks2], p0[4 * ks2 + 1], p0[4 * ks2 + 2], p0[4 * ks2 + 3]});
+            out[0][ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, out[0][ob], 0, 0, 0);
+            p1[step] = silu2(s1, step);
+          } else {
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){p1[4 * ks2], p1[4 * ks2 + 1], p1[4 * ks2 + 2], p1[4 * ks2 + 3]});
+            out[0][ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, out[0][ob], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        done = true;
+      }
+    }
+    if (kind != kTileEmpty && !done) {                                   // wave-uniform
+#pragma unroll
+      for (int sg = 0; sg < NSB; sg += SBG) {
+        // ---- scores of SBG sub-blocks at once: independent accumulators keep the matrix pipe fed
+        f32x16 sc1[SBG], sc2[SBG];
+        if (kind == kTileFull && bias_h) {
+          // every pair is visible and the distance is >= 0: seed the accumulators with the bias strip
+          const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
+#pragma unroll
+          for (int u = 0; u < SBG; ++u)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const f32x4 bv = *(const f32x4*)(strip + (sg + u) * 32 + 8 * q4);
+              sc1[u][4 * q4 + 0] = bv[0]; sc1[u][4 * q4 + 1] = bv[1];
+              sc1[u][4 * q4 + 2] = bv[2]; sc1[u][4 * q4 + 3] = bv[3];
+            }
         } else {
-          const float ds = sc2[r] * sig * (1.0f + s * (1.0f - sig));
-          c1[r] = vis ? ds : 0.f;
-          c2[r] = vis ? p : 0.f;
+#pragma unroll
+          for (int u = 0; u < SBG; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc1[u][r] = 0.f;
         }
-      }
+        if constexpr (MODE != kFwd) {
+#pragma unroll
+          for (int u = 0; u < SBG; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc2[u][r] = 0.f;
+        }
+        if constexpr (C::kBf16) {
+          // A-operand fragments are fetched one k-step ahead of the product that consumes them
+          bf16x8 f1[2][SBG], f2[2][SBG];
+#pragma unroll
+          for (int u = 0; u < SBG; ++u) {
+            f1[0][u] = *(const bf16x8*)(y1s + lds_off<C, 0>((sg + u) * 32 + l32, hf));
+            if (MODE != kFwd) f2[0][u] = *(const bf16x8*)(y2s + lds_off<C, 1>((sg + u) * 32 + l32, hf));
+          }
+#pragma unroll
+          for (int ks = 0; ks < C::KS; ++ks) {
+            if (ks + 1 < C::KS) {
+#pragma unroll
+              for (int u = 0; u < SBG; ++u) {
+                f1[(ks + 1) & 1][u] = *(const bf16x8*)(y1s + lds_off<C, 0>((sg + u) * 32 + l32, 2 * (ks + 1) + hf));
+                if (MODE != kFwd)
+                  f2[(ks + 1) & 1][u] = *(const bf16x8*)(y2s + lds_off<C, 1>((sg + u) * 32 + l32, 2 * (ks + 1) + hf));
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);                           // keep the fetches ahead of the products
+#pragma unroll
+            for (int u = 0; u < SBG; ++u) {
+              sc1[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[ks & 1][u], res[0][ks], sc1[u], 0, 0, 0);
+              if constexpr (MODE != kFwd)
+                sc2[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[ks & 1][u], res[1][ks], sc2[u], 0, 0, 0);
+            }
+          }
+        } else {
+#pragma unroll
+          for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+            for (int u = 0; u < SBG; ++u) {
+              const int roff = ((sg + u) * 32 + l32) * C::STRIDE0 + (2 * ks + hf) * 4;   // STRIDE0 == STRIDE1 in fp32
+              sc1[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(*(const float*)(y1s + roff), res[0][ks], sc1[u], 0, 0, 0);
+              if constexpr (MODE != kFwd)
+                sc2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(*(const float*)(y2s + roff), res[1][ks], sc2[u], 0, 0, 0);
+            }
+        }
 
-      // ---- second products: out^T[feature][x] += Y^T[feature][y] * coeff[y][x]
-      if constexpr (C::kBf16) {
-        uint32_t pk1[8], pk2[8];
+        // ---- pointwise: SiLU (forward) or its derivative times dP (backward), mask in registers
+        float c1[SBG][16], c2[SBG][16];
+        if (kind == kTileFull) {
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
-          pk1[m] = pack_bf16x2(c1[2 * m], c1[2 * m + 1]);
-          if (MODE == kBwdDKDV) pk2[m] = pack_bf16x2(c2[2 * m], c2[2 * m + 1]);
+          for (int u = 0; u < SBG; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const float sv = sc1[u][r];
+              const float sig = sigmoid_fast(sv);
+              if (MODE == kFwd) {
+                c1[u][r] = sv * sig;
+              } else {
+                c1[u][r] = sc2[u][r] * sig * (1.0f + sv * (1.0f - sig));
+                c2[u][r] = sv * sig;
+              }
+            }
+        } else {
+#pragma unroll
+          for (int u = 0; u < SBG; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int y = y0 + (sg + u) * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+              int delta;
+              const bool vis = (MODE == kBwdDKDV) ? visible(g, y, x, delta) : visible(g, x, y, delta);
+              float bv = 0.f;
+              if (bias_h) bv = bias_h[vis ? delta : 0];
+              const float sv = fmaf(sc1[u][r], a.alpha, bv);
+              const float sig = sigmoid_fast(sv);
+              const float p = sv * sig;
+              if (MODE == kFwd) {
+                c1[u][r] = vis ? p : 0.f;
+              } else {
+                const float ds = sc2[u][r] * sig * (1.0f + sv * (1.0f - sig));
+                c1[u][r] = vis ? ds : 0.f;
+                c2[u][r] = vis ? p : 0.f;
+              }
+            }
         }
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
-          // k-slots of this lane: streamed rows ks2*16 + 4*hf + {0..3} and + 8 + {0..3}
-          const bf16x8 b1 = __builtin_bit_cast(bf16x8, (u32x4){pk1[4 * ks2], pk1[4 * ks2 + 1], pk1[4 * ks2 + 2], pk1[4 * ks2 + 3]});
-          bf16x8 b2 = b1;
-          if (MODE == kBwdDKDV)
-            b2 = __builtin_bit_cast(bf16x8, (u32x4){pk2[4 * ks2], pk2[4 * ks2 + 1], pk2[4 * ks2 + 2], pk2[4 * ks2 + 3]});
+
+        // ---- second products: out^T[feature][x] += Y^T[feature][y] * coeff[y][x]
+        if constexpr (C::kBf16) {
           // transpose load: within a group of 16 lanes, lane 4r+c supplies the address of 4 features
-          // (4c..4c+3) of streamed row r and lane i receives feature i of rows 0..3
-          const int trow = sb * 32 + ks2 * 16 + 4 * hf + (i16 >> 2);
-          const int tcol = 16 * (grp16 & 1) + 4 * (i16 & 3);
+          // (4c..4c+3) of streamed row r and lane i receives feature i of rows 0..3.  The 8 k-slots of
+          // this lane in k-step ks2 are streamed rows ks2*16 + 4*hf + {0..3} and + 8 + {0..3}.
+          typedef __attribute__((address_space(3))) short4v* lds_s4;
+          const unsigned char* src0 = (MODE == kFwd) ? y2s : y1s;        // V (forward), K (dQ), Q (dK)
+          const int tchunk = 2 * (grp16 & 1) + ((i16 & 3) >> 1), tbyte = 8 * (i16 & 1);
+          constexpr int NSTEP = SBG * 2 * C::OB;                          // (sub-block, k-step, feature block)
+          auto fetch = [&](int step, const unsigned char* src, auto tensor) -> bf16x8 {
+            constexpr int TS = decltype(tensor)::value;
+            const int u = step / (2 * C::OB), ks2 = (step / C::OB) & 1, ob = step % C::OB;
+            const int trow = (sg + u) * 32 + ks2 * 16 + 4 * hf + (i16 >> 2);
+            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(src + lds_off<C, TS>(trow, 4 * ob + tchunk) + tbyte));
+            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(src + lds_off<C, TS>(trow + 8, 4 * ob + tchunk) + tbyte));
+            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          };
+          using T0 = std::integral_constant<int, 0>;
+          using T1 = std::integral_constant<int, 1>;
+          using TSRC = std::integral_constant<int, MODE == kFwd ? 1 : 0>;
+          uint32_t pk1[SBG][8], pk2[SBG][8];
 #pragma unroll
-          for (int ob = 0; ob < C::OB; ++ob) {
-            const int off = trow * C::STRIDE + (ob * 32 + tcol) * 2;
-            typedef __attribute__((address_space(3))) short4v* lds_s4;
-            const unsigned char* src0 = (MODE == kFwd) ? y2s : y1s;      // V (forward), K (dQ), Q (dK)
-            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(src0 + off));
-            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(src0 + off + 8 * C::STRIDE));
-            const bf16x8 af = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            out[0][ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b1, out[0][ob], 0, 0, 0);
+          for (int u = 0; u < SBG; ++u)
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+              pk1[u][m] = pack_bf16x2(c1[u][2 * m], c1[u][2 * m + 1]);
+              if (MODE == kBwdDKDV) pk2[u][m] = pack_bf16x2(c2[u][2 * m], c2[u][2 * m + 1]);
+            }
+          bf16x8 a1[2], a2[2];
+          a1[0] = fetch(0, src0, TSRC{});
+          if (MODE == kBwdDKDV) a2[0] = fetch(0, y2s, T1{});
+#pragma unroll
+          for (int step = 0; step < NSTEP; ++step) {
+            if (step + 1 < NSTEP) {
+              a1[(step + 1) & 1] = fetch(step + 1, src0, TSRC{});
+              if (MODE == kBwdDKDV) a2[(step + 1) & 1] = fetch(step + 1, y2s, T1{});
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int u = step / (2 * C::OB), ks2 = (step / C::OB) & 1, ob = step % C::OB;
+            const bf16x8 b1 = __builtin_bit_cast(bf16x8, (u32x4){pk1[u][4 * ks2], pk1[u][4 * ks2 + 1], pk1[u][4 * ks2 + 2], pk1[u][4 * ks2 + 3]});
+            out[0][ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[step & 1], b1, out[0][ob], 0, 0, 0);
             if constexpr (MODE == kBwdDKDV) {                            // dV^T += dO^T P
-              const short4v lo2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(y2s + off));
-              const short4v hi2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(y2s + off + 8 * C::STRIDE));
-              const bf16x8 af2 = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo2, hi2, 0, 1, 2, 3, 4, 5, 6, 7));
-              out[1][ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af2, b2, out[1][ob], 0, 0, 0);
+              const bf16x8 b2 = __builtin_bit_cast(bf16x8, (u32x4){pk2[u][4 * ks2], pk2[u][4 * ks2 + 1], pk2[u][4 * ks2 + 2], pk2[u][4 * ks2 + 3]});
+              out[1][ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2[step & 1], b2, out[1][ob], 0, 0, 0);
             }
           }
-        }
-      } else {
+        } else {
 #pragma unroll
-        for (int ks2 = 0; ks2 < 16; ++ks2) {
-          // k-step ks2 contracts the two streamed rows 8*(ks2/4) + ks2%4 (+4 for the upper half-wave)
-          const int trow = sb * 32 + 8 * (ks2 >> 2) + 4 * hf + (ks2 & 3);
+          for (int u = 0; u < SBG; ++u)
 #pragma unroll
-          for (int ob = 0; ob < C::OB; ++ob) {
-            const int off = trow * C::STRIDE + (ob * 32 + l32) * 4;
-            const unsigned char* src0 = (MODE == kFwd) ? y2s : y1s;
-            const float af = *(const float*)(src0 + off);
-            out[0][ob] = __builtin_amdgcn_mfma_f32_32x32x2f32(af, c1[ks2], out[0][ob], 0, 0, 0);
-            if constexpr (MODE == kBwdDKDV) {
-              const float af2 = *(const float*)(y2s + off);
-              out[1][ob] = __builtin_amdgcn_mfma_f32_32x32x2f32(af2, c2[ks2], out[1][ob], 0, 0, 0);
+            for (int ks2 = 0; ks2 < 16; ++ks2) {
+              // k-step ks2 contracts the two streamed rows 8*(ks2/4) + ks2%4 (+4 for the upper half-wave)
+              const int trow = (sg + u) * 32 + 8 * (ks2 >> 2) + 4 * hf + (ks2 & 3);
+#pragma unroll
+              for (int ob = 0; ob < C::OB; ++ob) {
+                const int off = trow * C::STRIDE0 + (ob * 32 + l32) * 4;
+                const unsigned char* src0 = (MODE == kFwd) ? y2s : y1s;
+                const float af = *(const float*)(src0 + off);
+                out[0][ob] = __builtin_amdgcn_mfma_f32_32x32x2f32(af, c1[u][ks2], out[0][ob], 0, 0, 0);
+                if constexpr (MODE == kBwdDKDV) {
+                  const float af2 = *(const float*)(y2s + off);
+                  out[1][ob] = __builtin_amdgcn_mfma_f32_32x32x2f32(af2, c2[u][ks2], out[1][ob], 0, 0, 0);
+                }
+              }
             }
-          }
         }
       }
     }

@@ -1,6 +1,7 @@
 """Parity of the HIP path (through the C ABI) against the CPU fp64 oracle, element by element,
-on the same seeded inputs.  Tolerances: max-abs error and max error normalised by the largest
-reference magnitude both <= 2e-2 for bf16 storage, <= 1e-5 for fp32."""
+on the same seeded inputs.  Tolerance tol = 2e-2 for bf16 storage, 1e-5 for fp32, applied to the
+max error normalised by the largest reference magnitude and to the max-abs error (the latter
+against tol * max(1, max|ref|): a bf16 output of magnitude 10 cannot be closer than 0.03)."""
 import numpy as np
 import pytest
 import torch
@@ -34,7 +35,7 @@ def check(name, got, ref, tol):
     scale = np.abs(ref).max()
     rel = err / scale if scale > 0 else err
     print(f"  {name}: max_abs_err={err:.3e} max|ref|={scale:.3e} normalised={rel:.3e}", flush=True)
-    assert err <= tol, f"{name}: max abs error {err:.3e} > {tol}"
+    assert err <= tol * max(1.0, scale), f"{name}: max abs error {err:.3e} > {tol * max(1.0, scale):.3e}"
     assert rel <= tol, f"{name}: normalised max error {rel:.3e} > {tol}"
 
 
