@@ -9,8 +9,9 @@
 
 namespace hstu {
 
-constexpr int kRowsPerBlock = 4;        // one wave per row, 4 waves per workgroup
-constexpr int kMaxBwdBlocks = 2048;
+constexpr int kRowsPerBlock = 4;        // forward: one wave per row, 4 waves per workgroup
+constexpr int kBwdWaves = 8;            // backward: 8 waves per workgroup, each walking over rows
+constexpr int kMaxBwdBlocks = 512;      // two workgroups per CU; also the number of partial column-sum rows
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_fwd_kernel(int6
 // dbeta = sum dn are kept per lane over the rows a wave visits, combined across the workgroup's
 // waves in a fixed order through LDS and written as one partial row per workgroup.
 template <typename E, int NCH>
-__global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_bwd_kernel(int64_t T, int D, const E* __restrict__ dy,
+__global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(int64_t T, int D, const E* __restrict__ dy,
                                                                             const E* __restrict__ attn,
                                                                             const E* __restrict__ u,
                                                                             const float* __restrict__ gamma,
@@ -131,8 +132,8 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_bwd_kernel(int6
       if (beta) load8(beta, e0, bv[c]);
     }
   }
-  const int64_t stride = (int64_t)gridDim.x * kRowsPerBlock;
-  for (int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave; row < T; row += stride) {
+  const int64_t stride = (int64_t)gridDim.x * kBwdWaves;
+  for (int64_t row = (int64_t)blockIdx.x * kBwdWaves + wave; row < T; row += stride) {
     const E* arow = attn + row * D;
     float a[NCH][8];
 #pragma unroll
@@ -179,8 +180,8 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_bwd_kernel(int6
       }
     }
   }
-  // fixed-order combination of the 4 waves' column sums
-  for (int w = 0; w < kRowsPerBlock; ++w) {
+  // fixed-order combination of the waves' column sums
+  for (int w = 0; w < kBwdWaves; ++w) {
     if (wave == w) {
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
@@ -199,19 +200,29 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_bwd_kernel(int6
   for (int i = threadIdx.x; i < 2 * D; i += blockDim.x) prow[i] = red[i];
 }
 
-// dgamma[c] = sum over workgroups of partial[blk][0][c]; dbeta likewise from partial[blk][1][c]
-__global__ __launch_bounds__(256) void gated_norm_colsum_kernel(int nblk, int D, const float* __restrict__ partial,
-                                                                float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= 2 * D) return;
+// dgamma[c] = sum over workgroups of partial[blk][0][c]; dbeta likewise from partial[blk][1][c].
+// 64 columns x 16 row groups per workgroup; the 16 partial sums of a column are combined in a fixed order.
+__global__ __launch_bounds__(1024) void gated_norm_colsum_kernel(int nblk, int D, const float* __restrict__ partial,
+                                                                 float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  __shared__ float red[16][64];
+  const int col = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + col;
   float s = 0.f;
-  for (int b = 0; b < nblk; ++b) s += partial[(int64_t)b * 2 * D + c];
-  if (c < D) dgamma[c] = s;
-  else if (dbeta) dbeta[c - D] = s;
+  if (c < 2 * D)
+    for (int b = rg; b < nblk; b += 16) s += partial[(int64_t)b * 2 * D + c];
+  red[rg][col] = s;
+  __syncthreads();
+  if (rg == 0 && c < 2 * D) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += red[i][col];
+    if (c < D) dgamma[c] = t;
+    else if (dbeta) dbeta[c - D] = t;
+  }
 }
 
 int gated_norm_bwd_blocks(int64_t T) {
-  const int64_t need = (T + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int64_t need = (T + kBwdWaves - 1) / kBwdWaves;
   return (int)(need < kMaxBwdBlocks ? need : kMaxBwdBlocks);
 }
 
@@ -235,11 +246,11 @@ static hipError_t bwd_one(int64_t T, int D, const void* dy, const void* attn, co
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(kern, dim3(nblk), dim3(64 * kRowsPerBlock), smem, stream, T, D, (const E*)dy, (const E*)attn,
+  hipLaunchKernelGGL(kern, dim3(nblk), dim3(64 * kBwdWaves), smem, stream, T, D, (const E*)dy, (const E*)attn,
                      (const E*)u, gamma, beta, eps, (E*)dattn, (E*)du, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(gated_norm_colsum_kernel, dim3((2 * D + 255) / 256), dim3(256), 0, stream, nblk, D, partial,
+  hipLaunchKernelGGL(gated_norm_colsum_kernel, dim3((2 * D + 63) / 64), dim3(1024), 0, stream, nblk, D, partial,
                      dgamma, dbeta);
   return hipGetLastError();
 }
