@@ -21,6 +21,11 @@ import numpy as np
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/attention_c3_dense_counters.md (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration
+# against a plain 1 GiB copy); only known for the workload that was profiled
+MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 1.318e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 1.413e9 + 0.104e9,
+                          ("C3-dense", "attn_bwd_dkdv"): 2.568e9 + 0.180e9}
 
 
 def parse():
@@ -33,6 +38,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward attention only (profiling aid)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (profiling aid: calibrates the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -99,6 +106,12 @@ def main():
         else:
             dw.attn_fwd()
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dw.device)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     ms_step = time_loop(step, args.steps, torch)
@@ -128,7 +141,7 @@ def main():
     dom = max((k for k in kern if k in algo), key=lambda k: kern[k])
     achieved = algo[dom] * w.d * fl["pairs"] / (kern[dom] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": None}
+                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))}
 
     sched = hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)
     eb = flops.epilogue_bytes(w)

@@ -1,0 +1,112 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: the HIP path runs
+the whole configuration, the CPU oracle recomputes a sample of token rows (all heads) one by one.
+Sampled rows: a seeded random set plus the rows where the tiling and the mask change behaviour
+(sequence starts and ends, workgroup block edges, window and prefix edges, first candidates)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hstu_oracle as orc
+from paper_2602_16986_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def sample_rows(w, n_random=40, seed=7):
+    rng = np.random.default_rng(seed)
+    rows = set(rng.integers(0, w.T, size=n_random).tolist())
+    for b in range(w.B):
+        s0, L = int(w.offsets[b]), int(w.lengths[b])
+        M = 0 if w.num_targets is None else int(w.num_targets[b])
+        local = [0, 1, 31, 32, 63, 64, 255, 256, 257, L - 1, L - 2, L // 2, (L // 256) * 256 - 1, (L // 256) * 256]
+        if w.K1 >= 0:
+            local += [w.K1 - 1, w.K1, w.K1 + 1, w.K2 - 1, w.K2, w.K2 + w.K1, L - w.K1]
+        if M:
+            local += [L - M - 1, L - M, L - M + 1, L - 1]
+        if b < 2 or b == w.B - 1:
+            rows.update(s0 + i for i in local if 0 <= i < L)
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def check(name, got, ref):
+    err = np.abs(got - ref).max()
+    scale = np.abs(ref).max()
+    print(f"  {name}: rows={ref.shape[0]} max_abs_err={err:.3e} max|ref|={scale:.3e} normalised={err / scale:.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert err <= TOL * max(1.0, scale) and err / scale <= TOL, name
+
+
+@pytest.mark.parametrize("name", ["C2", "C3-dense", "C3-sparse", "C4", "C5"])
+def test_full_size_sampled(name):
+    assert torch.cuda.is_available()
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.config(name)
+    print(f"config {name}: B={w.B} T={w.T} H={w.H} d={w.d} K1={w.K1} K2={w.K2}", flush=True)
+    dw = DeviceWorkload(w)
+    rows = sample_rows(w)
+    kw = dict(num_targets=w.num_targets, K1=w.K1, K2=w.K2, alpha=w.alpha, inv_n=1.0 / w.N, table=w.table,
+              bounds=w.bounds)
+    idx = torch.from_numpy(rows).to(dw.device)
+    f64 = lambda t: t.index_select(0, idx).float().cpu().numpy().astype(np.float64)
+    q, k, v, do = (x.astype(np.float64) for x in (w.q, w.k, w.v, w.dout))
+    dw.out.fill_(float("nan"))
+    dw.attn_fwd()
+    torch.cuda.synchronize()
+    print("  forward done on GPU", flush=True)
+    check("A", f64(dw.out), orc.attn_fwd(q, k, v, w.offsets, rows=rows, **kw))
+    assert torch.isfinite(dw.out.float()).all()
+    if w.backward:
+        for t in (dw.dq, dw.dk, dw.dv):
+            t.fill_(float("nan"))
+        dw.attn_bwd()
+        torch.cuda.synchronize()
+        print("  backward done on GPU", flush=True)
+        rq, rk, rv = orc.attn_bwd(q, k, v, do, w.offsets, rows=rows, **kw)
+        check("dQ", f64(dw.dq), rq)
+        check("dK", f64(dw.dk), rk)
+        check("dV", f64(dw.dv), rv)
+        for t in (dw.dq, dw.dk, dw.dv):
+            assert torch.isfinite(t.float()).all()
+    if name == "C5":
+        # the epilogue over every token, fed with the GPU's own attention output
+        dw.norm_fwd()
+        dw.norm_bwd()
+        torch.cuda.synchronize()
+        a_gpu = dw.out.float().cpu().numpy().astype(np.float64)
+        ry, _, _ = orc.gated_norm_fwd(a_gpu, w.u, w.gamma, None, w.eps)
+        got = dw.y.float().cpu().numpy().astype(np.float64)
+        check("Y", got.reshape(w.T, -1), ry.reshape(w.T, -1))
+        rda, rdu, rdg, _ = orc.gated_norm_bwd(w.dy, a_gpu, w.u, w.gamma, None, w.eps)
+        check("dA", dw.dattn.float().cpu().numpy().astype(np.float64).reshape(w.T, -1), rda.reshape(w.T, -1))
+        check("dU", dw.du.float().cpu().numpy().astype(np.float64).reshape(w.T, -1), rdu.reshape(w.T, -1))
+        check("dgamma", dw.dgamma.cpu().numpy().astype(np.float64), rdg)
+
+
+def test_causality_and_empty_sequences_on_gpu():
+    """Properties that hold at any size: perturbing later tokens leaves earlier rows bit-identical,
+    and zero-length sequences neither produce nor disturb output."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.build("prop", [700, 0, 300], 2, 128, "bf16", seed=3, K1=150, K2=40)
+    dw = DeviceWorkload(w)
+    base = dw.attn_fwd().clone()
+    torch.cuda.synchronize()
+    cut = 333
+    for t in (dw.q, dw.k, dw.v):
+        t[cut + 1:700] += 1.0
+    pert = dw.attn_fwd().clone()
+    torch.cuda.synchronize()
+    assert torch.equal(pert[:cut + 1], base[:cut + 1])
+    assert torch.equal(pert[700:], base[700:])
+    assert not torch.equal(pert[cut + 1:700], base[cut + 1:700])
+    # same batch without the empty sequence gives the same rows
+    w2 = wl.build("prop2", [700, 300], 2, 128, "bf16", seed=3, K1=150, K2=40)
+    w2.q, w2.k, w2.v, w2.table = w.q, w.k, w.v, w.table
+    out2 = DeviceWorkload(w2).attn_fwd()
+    torch.cuda.synchronize()
+    dw = DeviceWorkload(w)
+    assert torch.equal(out2, dw.attn_fwd())
+    # a window at least as long as the sequence equals dense causal
+    wd = wl.build("dense", [700, 0, 300], 2, 128, "bf16", seed=3)
+    ww = wl.build("wide", [700, 0, 300], 2, 128, "bf16", seed=3, K1=700, K2=0)
+    assert torch.equal(DeviceWorkload(wd).attn_fwd(), DeviceWorkload(ww).attn_fwd())
