@@ -70,7 +70,10 @@ typedef struct hstu_attn_params {
   int32_t total_tokens;     /* T = seq_offsets[B] */
   int32_t max_seqlen;       /* >= max_b L_b; sizes the expanded bias table and index ranges */
   int32_t dtype;            /* hstu_dtype of q, k, v, out, dout, dq, dk, dv */
-  int64_t row_stride_q;     /* elements between consecutive tokens of q (and of dq); >= H*d */
+  int64_t row_stride_q;     /* elements between consecutive tokens of q (and of dq); >= H*d, a multiple of 16 bytes,
+                               a row
+                               must span less than 16 MiB and (max_seqlen + 1) rows less than 4 GiB (else
+                               HSTU_ERR_UNSUPPORTED); max_seqlen < 2^24 */
   int64_t row_stride_k;     /* same for k / dk */
   int64_t row_stride_v;     /* same for v / dv */
   int64_t row_stride_o;     /* same for out / dout */

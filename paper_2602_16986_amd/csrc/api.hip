@@ -50,6 +50,12 @@ int validate(const hstu_attn_params* p) {
   const int64_t strides[4] = {p->row_stride_q, p->row_stride_k, p->row_stride_v, p->row_stride_o};
   for (int i = 0; i < 4; ++i)
     if (strides[i] < hd || strides[i] % quantum != 0) return HSTU_ERR_SHAPE;
+  // the kernels address a tile row as (sequence base) + 32-bit byte offset = 24-bit row * 24-bit stride
+  const int64_t esize = p->dtype == HSTU_BF16 ? 2 : 4;
+  if (p->max_seqlen >= 1 << 24) return HSTU_ERR_UNSUPPORTED;
+  for (int i = 0; i < 4; ++i)
+    if (strides[i] * esize >= 1 << 24 || strides[i] * esize * ((int64_t)p->max_seqlen + 1) >= (int64_t)1 << 32)
+      return HSTU_ERR_UNSUPPORTED;
   if (p->batch > 0 && !p->seq_offsets) return HSTU_ERR_NULL;
   if (p->global_prefix < 0) return HSTU_ERR_SHAPE;
   if ((p->rab_table == nullptr) != (p->rab_bounds == nullptr)) return HSTU_ERR_NULL;

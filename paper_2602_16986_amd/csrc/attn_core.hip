@@ -48,7 +48,14 @@ struct Cfg {
   //   tensor 0 (Y1): K in the forward (rows only), K in the dQ pass and Q in the dK/dV pass (both ways)
   //   tensor 1 (Y2): V in the forward (transposed only), V in the dQ pass (rows only), dO in dK/dV (both)
   static constexpr bool kBoth0 = MODE != kFwd, kBoth1 = MODE == kBwdDKDV;
-  static constexpr bool kSwz0 = kBf16 && D == 128 && kBoth0, kSwz1 = kBf16 && D == 128 && kBoth1;
+  // 4-wave query-stationary workgroups run two per compute unit (two independent instruction streams
+  // per SIMD): 256 registers per lane and half of the 160 KB of LDS each.
+  static constexpr bool kTwoPerCu = kBf16 && NWAVES == 4 && MODE != kBwdDKDV;
+  // 256-byte bf16 rows travel from global memory straight into LDS (no register staging): a wave-level
+  // 16-byte load places its 64 lanes in 1 KB of consecutive LDS, so those tiles are unpadded, and the
+  // swizzle (which each lane applies to its global address instead) serves both ways of reading them.
+  static constexpr bool kDma = kBf16 && D == 128;
+  static constexpr bool kSwz0 = kDma, kSwz1 = kDma;
   static constexpr int PAD0 = !kBf16 ? 16 : (kSwz0 ? 0 : (kBoth0 ? 80 : 16));
   static constexpr int PAD1 = !kBf16 ? 16 : (kSwz1 ? 0 : (kBoth1 ? 80 : (MODE == kFwd ? 64 : 16)));
   static constexpr int STRIDE0 = ROW_BYTES + PAD0, STRIDE1 = ROW_BYTES + PAD1;   // LDS row strides, bytes
@@ -66,6 +73,7 @@ struct Cfg {
   // fetch 4 consecutive entries with one aligned 16-byte LDS read.
   // Copy length = 16 (mod 64) entries keeps the 16 reads of a quarter-wave on 16 different bank groups.
   static constexpr int SLEN = (BX + BN + 4 - 16 + 63) / 64 * 64 + 16;   // entries per copy
+  static constexpr bool kStripDma = true;                        // strip: direct-to-LDS runs, or one register-staged entry per lane
   static constexpr int STRIP_BYTES = 4 * SLEN * 4;
   static constexpr int STRIP_BASE = 2 * STAGE_BYTES;
   static constexpr int SMEM_BYTES = 2 * STAGE_BYTES + 2 * STRIP_BYTES;  // 2 stages x (2 tensors + strip)
@@ -89,7 +97,7 @@ __device__ __forceinline__ float sigmoid_fast(float s) {
 }
 
 template <typename E, int D, int MODE, int NWAVES>
-__global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 2 : 1)) void attn_kernel(const AttnArgs a) {
   using C = Cfg<E, D, MODE, NWAVES>;
   using RFrag = typename ResidentFrag<E>::type;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -171,50 +179,126 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
   const int strip_s0 = C::BX - 1 - (wave * 32 + l32) + 4 * hf;
   const int strip_lane = (strip_s0 & 3) * C::SLEN + (strip_s0 & ~3);
 
-  // ---- global -> register -> LDS staging of the streamed tiles
+  // ---- staging of the streamed tiles: global -> LDS directly, or through registers
   u32x4 pre1[C::CPT], pre2[C::CPT];
   float pre_bias = 0.f;
+  const uint32_t rowb1 = (uint32_t)(sy1 * (int64_t)sizeof(E)), rowb2 = (uint32_t)(sy2 * (int64_t)sizeof(E));
+  // Tile loads are raw buffer loads: the descriptor (uniform, built on the scalar unit) carries the
+  // address of the piece's first row and the bytes left in the sequence from there, the lane supplies
+  // a loop-invariant 32-bit offset.  Rows past the sequence end are out of range and read as zero
+  // (every pair that involves them is masked anyway), and no vector arithmetic is needed per tile.
+  // The host checks that a sequence spans less than 4 GiB in every tensor.
+  static_assert(C::NT % C::CPR == 0 || C::CPT == 1, "a piece must cover whole tile rows");
+  static_assert(!C::kDma || (NWAVES % 4 == 0 && C::CPT * NWAVES * 4 == C::BN), "direct-to-LDS pieces are 4-row groups");
+  constexpr int PIECE_ROWS = C::NT / C::CPR;
+  // register-staged tiles: lane -> chunk tid of the piece.  Direct-to-LDS tiles: a wave fills the 4-row
+  // group rg = NWAVES * c + wave of the tile with piece c; lane -> row lane/16 of the group and LDS slot
+  // lane%16, which holds logical chunk slot ^ swz(row), swz(row) = 4 * (row%4) + (row/4)%4 = 4 * (lane/16) + wave%4.
+  const int dma_chunk = (lane & 15) ^ (4 * (lane >> 4) + (wave & 3));
+  uint32_t voff1 = C::kDma ? __umul24((uint32_t)(lane >> 4), rowb1) + (uint32_t)(dma_chunk * 16)
+                           : __umul24((uint32_t)(tid / C::CPR), rowb1) + (uint32_t)(tid % C::CPR * 16);
+  uint32_t voff2 = C::kDma ? __umul24((uint32_t)(lane >> 4), rowb2) + (uint32_t)(dma_chunk * 16)
+                           : __umul24((uint32_t)(tid / C::CPR), rowb2) + (uint32_t)(tid % C::CPR * 16);
+  asm volatile("" : "+v"(voff1), "+v"(voff2));
   // strip[s] = bias(distance) for s = (y - tile start) + (BX - 1 - (x - x0)); the distance grows with
-  // x - y in the query-stationary passes and with y - x in the key-stationary pass
-  auto gload = [&](int yt) {
-    if (bias_h) {
-      const int base = (MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) + tid : x0 + (C::BX - 1) - yt * C::BN - tid;
-      pre_bias = 0.f;
-      if (tid < C::BX + C::BN - 1 && base >= 0 && base < a.bias_stride) pre_bias = bias_h[base];
-    }
+  // x - y in the query-stationary passes and with y - x in the key-stationary pass.
+  // The bias strip goes to LDS the same direct way, 4 bytes per lane: the 4 * SLEN entries of a stage are 64-entry runs,
+  // run i = NWAVES * j + wave belongs to this wave.  Entry e = 64 * i + lane is position m = e % SLEN of copy
+  // c = e / SLEN and holds strip[m + c]; 4 * (m + c) is a loop invariant of the lane.
+  constexpr int STRIP_RUNS = 4 * C::SLEN / 64, STRIP_J = (STRIP_RUNS + NWAVES - 1) / NWAVES;
+  static_assert(4 * C::SLEN % 64 == 0, "strip stages are whole 64-entry runs");
+  uint32_t strip_s4[STRIP_J];
 #pragma unroll
-    for (int c = 0; c < C::CPT; ++c) {
-      const int idx = tid + c * C::NT;
-      const int row = idx / C::CPR, col = idx % C::CPR;
-      // rows past the sequence end re-read its last row: finite data, and every pair that involves
-      // them is masked (their coefficient is exactly zero)
-      const int y = min(yt * C::BN + row, L - 1);
-      if (C::CHUNKS % C::NT == 0 || idx < C::CHUNKS) {
-        pre1[c] = *(const u32x4*)((const unsigned char*)(Y1 + (int64_t)y * sy1) + col * 16);
-        pre2[c] = *(const u32x4*)((const unsigned char*)(Y2 + (int64_t)y * sy2) + col * 16);
-      }
+  for (int j = 0; j < STRIP_J; ++j) {
+    const int e = 64 * (NWAVES * j + wave) + lane;
+    strip_s4[j] = 4u * (uint32_t)(e % C::SLEN + e / C::SLEN);
+    asm volatile("" : "+v"(strip_s4[j]));
+  }
+  auto tile_rsrc = [&](const E* base, uint32_t rowb, int first_row) -> i32x4 {
+    const uint32_t left = (uint32_t)max(L - first_row, 0) * rowb;
+    const uint64_t addr = (uint64_t)(uintptr_t)base + (uint64_t)(uint32_t)first_row * rowb;
+    // raw buffer descriptor: 48-bit base, stride 0, bytes in range, 32-bit untyped data format
+    return (i32x4){(int)(uint32_t)addr, (int)((uint32_t)(addr >> 32) & 0xFFFFu), (int)left, 0x00020000};
+  };
+  // One 16-byte-per-lane load straight into LDS: lane l lands at LDS byte dst + 16 * l (dst uniform, passed
+  // in M0).  Written as one opaque instruction group so that the compiler does not order the LDS reads of
+  // the tile being consumed behind the arrival of the tile being fetched; lstore() below waits for the
+  // wave's own pieces and the workgroup barrier after it publishes them.
+  auto dma16 = [&](i32x4 rs, uint32_t voff, uint32_t dst) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(dst), "v"(voff), "s"(rs) : "memory", "m0");
+  };
+  auto dma4 = [&](i32x4 rs, uint32_t voff, uint32_t dst) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(dst), "v"(voff), "s"(rs) : "memory", "m0");
+  };
+  const uint64_t bias_addr = (uint64_t)(uintptr_t)bias_h;
+  const i32x4 bias_rs = {(int)(uint32_t)bias_addr, (int)((uint32_t)(bias_addr >> 32) & 0xFFFFu), a.bias_stride * 4, 0x00020000};
+  auto load16 = [&](const E* base, uint32_t rowb, int first_row, uint32_t voff) -> u32x4 {
+    const uint32_t left = (uint32_t)max(L - first_row, 0) * rowb;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((const unsigned char*)base + (uint64_t)(uint32_t)first_row * rowb), 0, (int)left, 0x00020000);
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, 0, 0);
+  };
+  // piece c of tile yt, bound for LDS stage `stage`
+  typedef __attribute__((address_space(3))) void* lds_void;
+  auto gload_piece = [&](int yt, int c, int stage) {
+    if (bias_h && C::kStripDma) {
+#pragma unroll
+      for (int j = 0; j < STRIP_J; ++j)
+        if (j % C::CPT == c && NWAVES * j + wave < STRIP_RUNS) {
+          // byte offset of table entry (distance of strip index s); entries outside [0, bias_stride) are
+          // out of range of the descriptor and read as zero
+          const int d0 = (MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) : x0 + (C::BX - 1) - yt * C::BN;
+          const uint32_t voff = (MODE == kBwdDKDV) ? (uint32_t)(4 * d0) + strip_s4[j] : (uint32_t)(4 * d0) - strip_s4[j];
+          const uint32_t dst = (uint32_t)(uintptr_t)(lds_void)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES + 256 * (NWAVES * j + wave));
+          dma4(bias_rs, voff, dst);
+        }
+    }
+    if (bias_h && !C::kStripDma && c == 0) {
+      const int d0 = (MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) : x0 + (C::BX - 1) - yt * C::BN;
+      const int base = (MODE == kBwdDKDV) ? d0 + tid : d0 - tid;
+      pre_bias = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(__builtin_amdgcn_make_buffer_rsrc((void*)bias_h, 0, a.bias_stride * 4, 0x00020000), base * 4, 0, 0));
+    }
+    if constexpr (C::kDma) {
+      const int rg = NWAVES * c + wave;
+      const uint32_t dst = (uint32_t)(uintptr_t)(lds_void)(smem + stage * C::STAGE_BYTES + rg * 1024);
+      dma16(tile_rsrc(Y1, rowb1, yt * C::BN + 4 * rg), voff1, dst);
+      dma16(tile_rsrc(Y2, rowb2, yt * C::BN + 4 * rg), voff2, dst + C::TILE0);
+    } else if (C::CHUNKS % C::NT == 0 || tid < C::CHUNKS) {
+      pre1[c] = load16(Y1, rowb1, yt * C::BN + c * PIECE_ROWS, voff1);
+      pre2[c] = load16(Y2, rowb2, yt * C::BN + c * PIECE_ROWS, voff2);
     }
   };
+  auto gload = [&](int yt, int stage) {
+#pragma unroll
+    for (int c = 0; c < C::CPT; ++c) gload_piece(yt, c, stage);
+  };
   auto lstore = [&](int stage) {
-    if (bias_h && tid < C::BX + C::BN - 1) {
+    if (bias_h && !C::kStripDma && tid < C::BX + C::BN - 1) {
       float* strip = (float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES);
 #pragma unroll
       for (int c = 0; c < 4; ++c)
         if (tid - c >= 0) strip[c * C::SLEN + tid - c] = pre_bias;        // copy c holds strip[m + c] at m
     }
+    // this wave's direct-to-LDS pieces (strip runs, 256-byte-row tiles) have landed once its load counter
+    // drains; the barrier that follows publishes them to the other waves
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (!C::kDma) {
 #pragma unroll
-    for (int c = 0; c < C::CPT; ++c) {
-      const int idx = tid + c * C::NT;
-      const int row = idx / C::CPR, col = idx % C::CPR;
-      if (C::CHUNKS % C::NT == 0 || idx < C::CHUNKS) {
-        *(u32x4*)(smem + stage * C::STAGE_BYTES + lds_off<C, 0>(row, col)) = pre1[c];
-        *(u32x4*)(smem + stage * C::STAGE_BYTES + C::TILE0 + lds_off<C, 1>(row, col)) = pre2[c];
+      for (int c = 0; c < C::CPT; ++c) {
+        const int idx = tid + c * C::NT;
+        const int row = idx / C::CPR, col = idx % C::CPR;
+        if (C::CHUNKS % C::NT == 0 || idx < C::CHUNKS) {
+          *(u32x4*)(smem + stage * C::STAGE_BYTES + lds_off<C, 0>(row, col)) = pre1[c];
+          *(u32x4*)(smem + stage * C::STAGE_BYTES + C::TILE0 + lds_off<C, 1>(row, col)) = pre2[c];
+        }
       }
     }
   };
 
   if (ntiles > 0) {
-    gload(tr.at(0));
+    gload(tr.at(0), 0);
     lstore(0);
   }
   __syncthreads();
@@ -224,7 +308,8 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
   for (int t = 0; t < ntiles; ++t) {
     const int yt = tr.at(t);
     const int stage = t & 1;
-    if (t + 1 < ntiles) gload(tr.at(t + 1));
+    const bool has_next = t + 1 < ntiles;
+    const int yt_next = has_next ? tr.at(t + 1) : 0;
     const unsigned char* y1s = smem + stage * C::STAGE_BYTES;
     const unsigned char* y2s = y1s + C::TILE0;
     const int y0 = yt * C::BN;
@@ -236,6 +321,12 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
     if (xw0 >= L) kind = kTileEmpty;
     if (kind == kTileFull && !unit_alpha) kind = kTilePartial;           // general alpha: generic path
 
+    // The next tile's global loads are issued piecewise between the score products: the compute unit's
+    // memory pipeline takes a 16-byte-per-lane load every few tens of cycles, and a wave that issues
+    // its whole share at once sits in that queue instead of feeding the matrix pipe.  A wave with
+    // nothing to compute issues them all now.
+    if (kind == kTileEmpty && has_next) gload(yt_next, stage ^ 1);
+
     bool done = false;
     if constexpr (MODE == kFwd && C::kBf16 && NSB == 2 && D == 128) {
       if (kind == kTileFull) {
@@ -245,8 +336,7 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
         //   S(0) | S(1) + SiLU(0) | PV(0) + SiLU(1) | PV(1)
         typedef __attribute__((address_space(3))) short4v* lds_s4;
         const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
-        const unsigned char* krow = y1s + l32 * C::STRIDE0 + hf * 16;                 // + sb*32*STRIDE0 + ks*32
-        const unsigned char* vtr = y2s + (4 * hf + (i16 >> 2)) * C::STRIDE1 + (2 * (grp16 & 1) + ((i16 & 3) >> 1)) * 16 + 8 * (i16 & 1);
+        const int vchunk = 2 * (grp16 & 1) + ((i16 & 3) >> 1), vbyte = 8 * (i16 & 1);
         auto seed = [&](int sb, f32x16& acc) {
           if (bias_h) {
 #pragma unroll
@@ -259,12 +349,12 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
           }
         };
-        auto kfrag = [&](int sb, int ks) -> bf16x8 { return *(const bf16x8*)(krow + sb * 32 * C::STRIDE0 + ks * 32); };
+        auto kfrag = [&](int sb, int ks) -> bf16x8 { return *(const bf16x8*)(y1s + lds_off<C, 0>(sb * 32 + l32, 2 * ks + hf)); };
         auto vfrag = [&](int sb, int step) -> bf16x8 {           // step = ks2 * OB + ob
           const int ks2 = step / C::OB, ob = step % C::OB;
-          const unsigned char* ptr = vtr + (sb * 32 + ks2 * 16) * C::STRIDE1 + ob * 64;
-          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)ptr);
-          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(ptr + 8 * C::STRIDE1));
+          const int vrow = sb * 32 + ks2 * 16 + 4 * hf + (i16 >> 2);
+          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(y2s + lds_off<C, 1>(vrow, 4 * ob + vchunk) + vbyte));
+          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(y2s + lds_off<C, 1>(vrow + 8, 4 * ob + vchunk) + vbyte));
           return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         };
         auto silu2 = [&](const f32x16& sc, int m) -> uint32_t {   // elements 2m, 2m+1 -> packed bf16 pair
@@ -286,6 +376,7 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
         for (int n = 0; n < 16; ++n) {
           const bf16x8 fa = kf[n % PF];
           if (n + PF < 16) kf[n % PF] = kfrag((n + PF) / 8, (n + PF) % 8);
+          if (has_next && n % (16 / C::CPT) == 0) gload_piece(yt_next, n / (16 / C::CPT), stage ^ 1);
           __builtin_amdgcn_sched_barrier(0);
           if (n < 8) {
             s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, res[0][n], s0, 0, 0, 0);
@@ -364,6 +455,11 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
                   f2[(ks + 1) & 1][u] = *(const bf16x8*)(y2s + lds_off<C, 1>((sg + u) * 32 + l32, 2 * (ks + 1) + hf));
               }
             }
+            if constexpr (C::KS % C::CPT == 0) {
+              if (sg == 0 && has_next && ks % (C::KS / C::CPT) == 0) gload_piece(yt_next, ks / (C::KS / C::CPT), stage ^ 1);
+            } else {
+              if (sg == 0 && has_next && ks == 0) gload(yt_next, stage ^ 1);
+            }
             __builtin_amdgcn_sched_barrier(0);                           // keep the fetches ahead of the products
 #pragma unroll
             for (int u = 0; u < SBG; ++u) {
@@ -373,6 +469,7 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
             }
           }
         } else {
+          if (sg == 0 && has_next) gload(yt_next, stage ^ 1);
 #pragma unroll
           for (int ks = 0; ks < C::KS; ++ks)
 #pragma unroll
@@ -492,7 +589,7 @@ __global__ __launch_bounds__(64 * NWAVES) void attn_kernel(const AttnArgs a) {
       }
     }
 
-    if (t + 1 < ntiles) lstore(stage ^ 1);
+    if (has_next) lstore(stage ^ 1);
     __syncthreads();
   }
 
@@ -560,8 +657,8 @@ static hipError_t dispatch(const AttnArgs& a, int dtype, hipStream_t stream) {
   return hipErrorInvalidValue;
 }
 
-constexpr int kFwdWavesBf16 = 8, kFwdWavesFp32 = 4;
-constexpr int kDqWavesBf16 = 8, kDqWavesFp32 = 4;
+constexpr int kFwdWavesBf16 = 4, kFwdWavesFp32 = 4;
+constexpr int kDqWavesBf16 = 4, kDqWavesFp32 = 4;
 constexpr int kDkvWavesBf16 = 4, kDkvWavesFp32 = 4;
 
 int fwd_block_rows(int dtype, int) { return 32 * (dtype == 0 ? kFwdWavesBf16 : kFwdWavesFp32); }

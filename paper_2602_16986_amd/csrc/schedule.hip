@@ -57,8 +57,9 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
 
   // 2. natural order: sequence-major, then head, then block index descending.  Item idx -> (b, h, rb).
   const bool sorted = total <= kSortMax;
-  // a run of kXcdGroup neighbouring blocks differs by about kXcdGroup * block_rows / tile_cols tiles
-  const int cost_quantum = max(1, kXcdGroup * block_rows / tile_cols);
+  // exact longest-first order measured best: the heaviest block is half of one compute unit's whole
+  // share on the 8k-16k workload, so any coarsening of the order shows up as tail imbalance
+  const int cost_quantum = 1;
   unsigned long long my_tiles = 0, my_dense = 0;
   for (int idx = tid; idx < total; idx += kSchedThreads) {
     // find b with seq_base[b]*H <= idx < seq_base[b+1]*H
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     my_tiles += cost;
     my_dense += (L + tile_cols - 1) / tile_cols;
     if (sorted) {
-      // quantised so that runs of neighbouring blocks of one (sequence, head) keep their natural order
+      // ties keep the natural order: the heads of one (sequence, block) stay adjacent
       const uint32_t cq = min((uint32_t)cost / (uint32_t)cost_quantum, 0x7FFFFu);
       keys[idx] = ((0x7FFFFu - cq) << 13) | (uint32_t)idx;        // idx < 8192 = 2^13
     } else {
