@@ -409,6 +409,100 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
         done = true;
       }
     }
+    if constexpr (MODE != kFwd && C::kBf16 && NSB == 2 && D == 128) {
+      if (kind == kTileFull) {
+        // Software-pipelined backward for fully visible tiles, same idea as the forward: the pointwise
+        // work of one 32-row sub-block (SiLU, its derivative, packing) is issued between the matrix
+        // instructions that do not depend on it:
+        //   S,dP(0) | S,dP(1) + pointwise(0) | outputs(0) + pointwise(1) | outputs(1)
+        // outputs = dQ^T += K^T dS^T (dQ pass) or dK^T += Q^T dS, dV^T += dO^T P (dK/dV pass).
+        typedef __attribute__((address_space(3))) short4v* lds_s4;
+        static_assert(C::kSwz0 && C::kSwz1 && C::STRIDE0 == C::STRIDE1, "both tiles share one layout here");
+        const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
+        const int vchunk = 2 * (grp16 & 1) + ((i16 & 3) >> 1), vbyte = 8 * (i16 & 1);
+        // LDS addresses are formed next to each read with one XOR instead of being kept as loop invariants
+        // (one register per k-step / feature block otherwise).  For tile row r = 32*sb + l32 the swizzle is a
+        // lane constant z, and chunk 2*ks+hf lands at byte 256*r + 16*((2*ks+hf)^z) = 8192*sb + (kb ^ 32*ks).
+        // For the transpose reads (row R + 4*hf + i16/4 + 8*hi, R a multiple of 16, chunk 4*ob + vchunk)
+        // z = 4*(i16/4) + hf + 2*hi and the byte is 256*R + 2048*hi + (tb ^ (64*ob | 32*hi)).
+        const int zl = 4 * (l32 & 3) + ((l32 >> 2) & 3);
+        int kb = stage * C::STAGE_BYTES + l32 * 256 + ((hf ^ (zl & 1)) << 4) + ((zl >> 1) << 5);
+        int tb = stage * C::STAGE_BYTES + (4 * hf + (i16 >> 2)) * 256 + ((i16 >> 2) << 6) + ((vchunk ^ hf) << 4) + vbyte;
+        asm volatile("" : "+v"(kb), "+v"(tb));
+        // score fragment n: tensor n%2 (S then dP), sub-block n/16, k-step (n/2)%8
+        auto rowfrag = [&](int n) -> bf16x8 {
+          return *(const bf16x8*)(smem + (kb ^ (((n >> 1) & 7) << 5)) + (n >> 4) * 8192 + (n & 1) * C::TILE0);
+        };
+        // output fragment n: sub-block n / (8*NOUT), then (k-step, feature block) major, output minor
+        auto trfrag = [&](int n) -> bf16x8 {
+          const int sb = n / (8 * C::NOUT), r = n % (8 * C::NOUT), step = r / C::NOUT, o = r % C::NOUT;
+          const int ks2 = step / C::OB, ob = step % C::OB;
+          const int roff = (sb * 32 + ks2 * 16) * 256 + o * C::TILE0;
+          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (tb ^ (ob << 6)) + roff));
+          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (tb ^ ((ob << 6) | 32)) + roff + 2048));
+          return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
+        f32x16 sv[2], dp[2];
+        uint32_t pds[2][8], pp[2][8];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+          if (bias_h) {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const f32x4 bv = *(const f32x4*)(strip + sb * 32 + 8 * q4);
+              sv[sb][4 * q4 + 0] = bv[0]; sv[sb][4 * q4 + 1] = bv[1]; sv[sb][4 * q4 + 2] = bv[2]; sv[sb][4 * q4 + 3] = bv[3];
+            }
+          } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sv[sb][r] = 0.f;
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dp[sb][r] = 0.f;
+        }
+        // elements 2m, 2m+1 of sub-block sb -> packed pairs of dS (and of P for the dK/dV pass);
+        // sig (1 + s (1 - sig)) = sig + p (1 - sig)
+        auto pointwise = [&](int sb, int m) {
+          const float s0v = sv[sb][2 * m], s1v = sv[sb][2 * m + 1];
+          const float g0 = sigmoid_fast(s0v), g1 = sigmoid_fast(s1v);
+          const float p0v = s0v * g0, p1v = s1v * g1;
+          pds[sb][m] = pack_bf16x2(dp[sb][2 * m] * fmaf(p0v, 1.0f - g0, g0), dp[sb][2 * m + 1] * fmaf(p1v, 1.0f - g1, g1));
+          if constexpr (MODE == kBwdDKDV) pp[sb][m] = pack_bf16x2(p0v, p1v);
+        };
+        constexpr int PF = (MODE == kBwdDQ) ? 2 : 4;                      // the dQ pass runs two waves per SIMD: 256 registers
+        bf16x8 fr[PF];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) fr[i] = rowfrag(i);
+#pragma unroll
+        for (int n = 0; n < 32; ++n) {
+          const bf16x8 fa = fr[n % PF];
+          if (n + PF < 32) fr[n % PF] = rowfrag(n + PF);
+          if (has_next && n % (32 / C::CPT) == 0) gload_piece(yt_next, n / (32 / C::CPT), stage ^ 1);
+          __builtin_amdgcn_sched_barrier(0);
+          const int sb = n >> 4, ks = (n >> 1) & 7;
+          if (n & 1) dp[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, res[1][ks], dp[sb], 0, 0, 0);
+          else sv[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, res[0][ks], sv[sb], 0, 0, 0);
+          if (n >= 16 && (n & 1)) pointwise(0, (n - 16) >> 1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        constexpr int NO = 16 * C::NOUT;                                  // output products of the tile
+#pragma unroll
+        for (int i = 0; i < PF; ++i) fr[i] = trfrag(i);
+#pragma unroll
+        for (int n = 0; n < NO; ++n) {
+          const bf16x8 fa = fr[n % PF];
+          if (n + PF < NO) fr[n % PF] = trfrag(n + PF);
+          __builtin_amdgcn_sched_barrier(0);
+          const int sb = n / (8 * C::NOUT), r = n % (8 * C::NOUT), step = r / C::NOUT, o = r % C::NOUT;
+          const int ks2 = step / C::OB, ob = step % C::OB;
+          const uint32_t* pk = (o == 0) ? pds[sb] : pp[sb];
+          const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){pk[4 * ks2], pk[4 * ks2 + 1], pk[4 * ks2 + 2], pk[4 * ks2 + 3]});
+          out[o][ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, pb, out[o][ob], 0, 0, 0);
+          if (sb == 0 && o == C::NOUT - 1) pointwise(1, step);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        done = true;
+      }
+    }
     if (kind != kTileEmpty && !done) {                                   // wave-uniform
 #pragma unroll
       for (int sg = 0; sg < NSB; sg += SBG) {
