@@ -91,10 +91,16 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
   else return row * stride + (chunk << 4);
 }
 
-__device__ __forceinline__ float sigmoid_fast(float s) {
-  const float e = __builtin_amdgcn_exp2f(s * -1.4426950408889634f);
-  return __builtin_amdgcn_rcpf(1.0f + e);
+// Scores are kept in units of ln 2 inside the kernels (t = s * log2 e): the stationary operand of the
+// score product and the expanded bias table are scaled by log2 e once, so the sigmoid needs no multiply
+// in front of its exp2, and the ln 2 that P = s * sigmoid(s) = ln2 * t * sigmoid owes is folded into the
+// output scale (forward, dV) or into the (1 - sigmoid) term (dS).
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+__device__ __forceinline__ float sigmoid_l2(float t) {           // sigmoid(t * ln 2)
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
 }
+// dS / dP = sigmoid (1 + s (1 - sigmoid)) = sigmoid + (t sigmoid) * ln2 (1 - sigmoid)
+__device__ __forceinline__ float dsilu_l2(float tp, float sig) { return fmaf(tp, fmaf(-kLn2, sig, kLn2), sig); }
 
 template <typename E, int D, int MODE, int NWAVES>
 __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 2 : 1)) void attn_kernel(const AttnArgs a) {
@@ -148,9 +154,15 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
       if constexpr (C::kBf16) {
         u32x4 raw = {0u, 0u, 0u, 0u};
         if (x_ok) raw = *(const u32x4*)(rp + ks * 16 + hf * 8);
+        if (i == 0) {                                                    // operand of the score product: times log2 e
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            raw[w] = pack_bf16x2(__builtin_bit_cast(float, raw[w] << 16) * kLog2e,
+                                 __builtin_bit_cast(float, raw[w] & 0xFFFF0000u) * kLog2e);
+        }
         res[i][ks] = __builtin_bit_cast(RFrag, raw);
       } else {
-        res[i][ks] = x_ok ? rp[2 * ks + hf] : 0.f;
+        res[i][ks] = x_ok ? rp[2 * ks + hf] * (i == 0 ? kLog2e : 1.0f) : 0.f;
       }
     }
   }
@@ -359,7 +371,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
         };
         auto silu2 = [&](const f32x16& sc, int m) -> uint32_t {   // elements 2m, 2m+1 -> packed bf16 pair
           const float s0v = sc[2 * m], s1v = sc[2 * m + 1];
-          return pack_bf16x2(s0v * sigmoid_fast(s0v), s1v * sigmoid_fast(s1v));
+          return pack_bf16x2(s0v * sigmoid_l2(s0v), s1v * sigmoid_l2(s1v));
         };
         // LDS fragments are fetched PF products ahead of their use: the latency of an LDS read is
         // several matrix instructions long
@@ -460,12 +472,11 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
           for (int r = 0; r < 16; ++r) dp[sb][r] = 0.f;
         }
         // elements 2m, 2m+1 of sub-block sb -> packed pairs of dS (and of P for the dK/dV pass);
-        // sig (1 + s (1 - sig)) = sig + p (1 - sig)
         auto pointwise = [&](int sb, int m) {
           const float s0v = sv[sb][2 * m], s1v = sv[sb][2 * m + 1];
-          const float g0 = sigmoid_fast(s0v), g1 = sigmoid_fast(s1v);
+          const float g0 = sigmoid_l2(s0v), g1 = sigmoid_l2(s1v);
           const float p0v = s0v * g0, p1v = s1v * g1;
-          pds[sb][m] = pack_bf16x2(dp[sb][2 * m] * fmaf(p0v, 1.0f - g0, g0), dp[sb][2 * m + 1] * fmaf(p1v, 1.0f - g1, g1));
+          pds[sb][m] = pack_bf16x2(dp[sb][2 * m] * dsilu_l2(p0v, g0), dp[sb][2 * m + 1] * dsilu_l2(p1v, g1));
           if constexpr (MODE == kBwdDKDV) pp[sb][m] = pack_bf16x2(p0v, p1v);
         };
         constexpr int PF = (MODE == kBwdDQ) ? 2 : 4;                      // the dQ pass runs two waves per SIMD: 256 registers
@@ -583,11 +594,11 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const float sv = sc1[u][r];
-              const float sig = sigmoid_fast(sv);
+              const float sig = sigmoid_l2(sv);
               if (MODE == kFwd) {
                 c1[u][r] = sv * sig;
               } else {
-                c1[u][r] = sc2[u][r] * sig * (1.0f + sv * (1.0f - sig));
+                c1[u][r] = sc2[u][r] * dsilu_l2(sv * sig, sig);
                 c2[u][r] = sv * sig;
               }
             }
@@ -602,12 +613,12 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
               float bv = 0.f;
               if (bias_h) bv = bias_h[vis ? delta : 0];
               const float sv = fmaf(sc1[u][r], a.alpha, bv);
-              const float sig = sigmoid_fast(sv);
+              const float sig = sigmoid_l2(sv);
               const float p = sv * sig;
               if (MODE == kFwd) {
                 c1[u][r] = vis ? p : 0.f;
               } else {
-                const float ds = sc2[u][r] * sig * (1.0f + sv * (1.0f - sig));
+                const float ds = sc2[u][r] * dsilu_l2(p, sig);
                 c1[u][r] = vis ? ds : 0.f;
                 c2[u][r] = vis ? p : 0.f;
               }
@@ -694,10 +705,10 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     E* dst;
     int64_t sd;
     float scale;
-    if (MODE == kFwd) { dst = (E*)a.out; sd = a.so; scale = a.inv_n; }
+    if (MODE == kFwd) { dst = (E*)a.out; sd = a.so; scale = a.inv_n * kLn2; }
     else if (MODE == kBwdDQ) { dst = (E*)a.dq; sd = a.sq; scale = a.inv_n * a.alpha; }
     else if (o == 0) { dst = (E*)a.dk; sd = a.sk; scale = a.inv_n * a.alpha; }
-    else { dst = (E*)a.dv; sd = a.sv; scale = a.inv_n; }
+    else { dst = (E*)a.dv; sd = a.sv; scale = a.inv_n * kLn2; }
     dst += (int64_t)(seq0 + x) * sd + hoff;
 #pragma unroll
     for (int ob = 0; ob < C::OB; ++ob)

@@ -140,7 +140,8 @@ hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, boo
   return hipGetLastError();
 }
 
-// bias_by_distance[h, x] = table[h, bucket(x)], bucket(x) = max{c : bounds[c] <= x}, for x in [0, len).
+// bias_by_distance[h, x] = log2(e) * table[h, bucket(x)], bucket(x) = max{c : bounds[c] <= x}, for x in [0, len):
+// the attention kernels keep their scores in units of ln 2.
 __global__ __launch_bounds__(256) void bias_expand_kernel(const float* __restrict__ table,
                                                           const int32_t* __restrict__ bounds, int nb, int H, int len,
                                                           float* __restrict__ out) {
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(256) void bias_expand_kernel(const float* __restric
     const int mid = (lo + hi) >> 1;
     if (bounds[mid] <= x) lo = mid; else hi = mid;
   }
-  for (int h = 0; h < H; ++h) out[(size_t)h * len + x] = table[(size_t)h * nb + lo];
+  for (int h = 0; h < H; ++h) out[(size_t)h * len + x] = table[(size_t)h * nb + lo] * 1.4426950408889634f;
 }
 
 hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
