@@ -230,7 +230,7 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
     const int rows = s == 0 ? dq_block_rows(p->dtype, p->head_dim) : dkv_block_rows(p->dtype, p->head_dim);
     {
       ProfScope ps(s == 0 ? "schedule_dq" : "schedule_dkdv", stream);
-      if (launch_schedule(a, rows, tile, s == 1, (SchedHeader*)(ws + l.header[s]), (WorkItem*)(ws + l.items[s]),
+      if (launch_schedule(a, rows, s == 1 ? dkv_tile_rows(p->dtype, p->head_dim) : tile, s == 1, (SchedHeader*)(ws + l.header[s]), (WorkItem*)(ws + l.items[s]),
                           (int32_t*)(ws + l.seq_base[s]), stream) != hipSuccess)
         return HSTU_ERR_LAUNCH;
     }

@@ -34,7 +34,11 @@ template <typename E, int D, int MODE, int NWAVES>
 struct Cfg {
   static constexpr bool kBf16 = sizeof(E) == 2;
   static constexpr int BX = 32 * NWAVES;                        // stationary rows per workgroup
-  static constexpr int BN = kBf16 ? 64 : 32;                    // streamed rows per LDS tile
+  // dK/dV pass with 128 features: the accumulators alone take 128 registers per lane, so the V rows of the
+  // workgroup's keys stay in LDS (not in registers) and the streamed tiles are 32 rows; that fits 256
+  // registers and half the LDS, i.e. two workgroups per compute unit like the other passes.
+  static constexpr bool kStatLds = kBf16 && D == 128 && MODE == kBwdDKDV;
+  static constexpr int BN = kBf16 ? (kStatLds ? 32 : 64) : 32;  // streamed rows per LDS tile
   static constexpr int NT = 64 * NWAVES;
   static constexpr int ROW_BYTES = D * (int)sizeof(E);
   // LDS tiles are read two ways: 16-byte reads with one streamed row per lane (score products)
@@ -50,7 +54,7 @@ struct Cfg {
   static constexpr bool kBoth0 = MODE != kFwd, kBoth1 = MODE == kBwdDKDV;
   // 4-wave query-stationary workgroups run two per compute unit (two independent instruction streams
   // per SIMD): 256 registers per lane and half of the 160 KB of LDS each.
-  static constexpr bool kTwoPerCu = kBf16 && NWAVES == 4 && MODE != kBwdDKDV;
+  static constexpr bool kTwoPerCu = kBf16 && NWAVES == 4 && (MODE != kBwdDKDV || kStatLds);
   // 256-byte bf16 rows travel from global memory straight into LDS (no register staging): a wave-level
   // 16-byte load places its 64 lanes in 1 KB of consecutive LDS, so those tiles are unpadded, and the
   // swizzle (which each lane applies to its global address instead) serves both ways of reading them.
@@ -64,7 +68,8 @@ struct Cfg {
   static constexpr int CPR = ROW_BYTES / 16;                    // 16-byte chunks per row
   static constexpr int CHUNKS = BN * CPR;
   static constexpr int CPT = (CHUNKS + NT - 1) / NT;            // chunks per thread per tensor
-  static constexpr int NRES = (MODE == kFwd) ? 1 : 2;           // resident operands
+  static constexpr int NRES = (MODE == kFwd) ? 1 : 2;           // stationary operands
+  static constexpr int NREG = kStatLds ? 1 : NRES;              // ... of which in registers
   static constexpr int NOUT = (MODE == kBwdDKDV) ? 2 : 1;       // output accumulators
   static constexpr int KS = kBf16 ? D / 16 : D / 2;             // k-steps of a score product
   static constexpr int OB = D / 32;                             // 32-feature output blocks
@@ -76,7 +81,9 @@ struct Cfg {
   static constexpr bool kStripDma = true;                        // strip: direct-to-LDS runs, or one register-staged entry per lane
   static constexpr int STRIP_BYTES = 4 * SLEN * 4;
   static constexpr int STRIP_BASE = 2 * STAGE_BYTES;
-  static constexpr int SMEM_BYTES = 2 * STAGE_BYTES + 2 * STRIP_BYTES;  // 2 stages x (2 tensors + strip)
+  static constexpr int STAT_BASE = 2 * STAGE_BYTES + 2 * STRIP_BYTES;
+  static constexpr int STAT_BYTES = kStatLds ? BX * ROW_BYTES : 0;      // stationary operand 1, same swizzle as the tiles
+  static constexpr int SMEM_BYTES = STAT_BASE + STAT_BYTES;             // 2 stages x (2 tensors + strip) [+ stationary rows]
 };
 
 template <typename E> struct ResidentFrag;
@@ -147,7 +154,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
   // ---- resident operands (B operands: lane = row x, registers = 8 (bf16) or 1 (fp32) features per k-step)
   RFrag res[C::NRES][C::KS];
 #pragma unroll
-  for (int i = 0; i < C::NRES; ++i) {
+  for (int i = 0; i < C::NREG; ++i) {
     const E* rp = (i == 0 ? R1 + (int64_t)x * sr1 : R2 + (int64_t)x * sr2);
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
@@ -170,7 +177,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
   // The resident operands must have landed before the tile loop: inside it the only global loads
   // in flight are the next tile's, and nothing may force a wait on those before they are needed.
 #pragma unroll
-  for (int i = 0; i < C::NRES; ++i)
+  for (int i = 0; i < C::NREG; ++i)
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+v"(res[i][ks]));
 
@@ -309,10 +316,20 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     }
   };
 
-  if (ntiles > 0) {
-    gload(tr.at(0), 0);
-    lstore(0);
+  if constexpr (C::kStatLds) {
+    // this wave's 32 stationary rows of operand 1 (V), straight to LDS; only this wave reads them back
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int rg = wave * 8 + j;                                       // 4-row group inside the block
+      const int chunk = (lane & 15) ^ (4 * (lane >> 4) + (rg & 3));
+      const uint32_t rowb = (uint32_t)(sr2 * (int64_t)sizeof(E));
+      const uint32_t voff = __umul24((uint32_t)(lane >> 4), rowb) + (uint32_t)(chunk * 16);
+      const uint32_t dst = (uint32_t)(uintptr_t)(lds_void)(smem + C::STAT_BASE + rg * 1024);
+      dma16(tile_rsrc(R2, rowb, x0 + 4 * rg), voff, dst);
+    }
   }
+  if (ntiles > 0) gload(tr.at(0), 0);
+  lstore(0);
   __syncthreads();
 
   constexpr int NSB = C::BN / 32;                     // 32-row sub-blocks of a streamed tile
@@ -339,6 +356,47 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     // nothing to compute issues them all now.
     if (kind == kTileEmpty && has_next) gload(yt_next, stage ^ 1);
 
+    // Swizzled (direct-to-LDS) tiles: LDS addresses are formed next to each read with one XOR instead of
+    // being kept as loop invariants (one register per k-step / feature block otherwise).  For tile row
+    // r = 32*sub + l32 the swizzle is a lane constant z, and chunk 2*ks+hf lands at byte
+    // 256*r + 16*((2*ks+hf)^z) = 8192*sub + (kb ^ 32*ks).  For the transpose reads (row R + 4*hf + i16/4 + 8*hi,
+    // R a multiple of 16, chunk 4*ob + vchunk) z = 4*(i16/4) + hf + 2*hi and the byte is
+    // 256*R + 2048*hi + (tb ^ (64*ob | 32*hi)).
+    const int vchunk = 2 * (grp16 & 1) + ((i16 & 3) >> 1), vbyte = 8 * (i16 & 1);
+    const int zl = 4 * (l32 & 3) + ((l32 >> 2) & 3);
+    int kb = stage * C::STAGE_BYTES + l32 * 256 + ((hf ^ (zl & 1)) << 4) + ((zl >> 1) << 5);
+    int tb = stage * C::STAGE_BYTES + (4 * hf + (i16 >> 2)) * 256 + ((i16 >> 2) << 6) + ((vchunk ^ hf) << 4) + vbyte;
+    asm volatile("" : "+v"(kb), "+v"(tb));
+    typedef __attribute__((address_space(3))) short4v* lds_s4;
+    // row fragment (A operand of a score product): tensor, 32-row sub-block, k-step
+    auto rowfrag_at = [&](int tensor, int sub, int ks) -> bf16x8 {
+      if constexpr (C::kDma) {
+        return *(const bf16x8*)(smem + (kb ^ (ks << 5)) + sub * 8192 + tensor * C::TILE0);
+      } else {
+        return tensor == 0 ? *(const bf16x8*)(y1s + lds_off<C, 0>(sub * 32 + l32, 2 * ks + hf))
+                           : *(const bf16x8*)(y2s + lds_off<C, 1>(sub * 32 + l32, 2 * ks + hf));
+      }
+    };
+    // transposed fragment (A operand of an output product): tensor, sub-block, 16-row k-step, feature block
+    auto trfrag_at = [&](int tensor, int sub, int ks2, int ob) -> bf16x8 {
+      short4v lo, hi;
+      if constexpr (C::kDma) {
+        const int roff = (sub * 32 + ks2 * 16) * 256 + tensor * C::TILE0;
+        lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (tb ^ (ob << 6)) + roff));
+        hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (tb ^ ((ob << 6) | 32)) + roff + 2048));
+      } else {
+        const int trow = sub * 32 + ks2 * 16 + 4 * hf + (i16 >> 2);
+        if (tensor == 0) {
+          lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(y1s + lds_off<C, 0>(trow, 4 * ob + vchunk) + vbyte));
+          hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(y1s + lds_off<C, 0>(trow + 8, 4 * ob + vchunk) + vbyte));
+        } else {
+          lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(y2s + lds_off<C, 1>(trow, 4 * ob + vchunk) + vbyte));
+          hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(y2s + lds_off<C, 1>(trow + 8, 4 * ob + vchunk) + vbyte));
+        }
+      }
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
     bool done = false;
     if constexpr (MODE == kFwd && C::kBf16 && NSB == 2 && D == 128) {
       if (kind == kTileFull) {
@@ -346,9 +404,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
         // issued between the matrix instructions of the next product, so the matrix pipe and the
         // vector ALU of this wave work at the same time:
         //   S(0) | S(1) + SiLU(0) | PV(0) + SiLU(1) | PV(1)
-        typedef __attribute__((address_space(3))) short4v* lds_s4;
         const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
-        const int vchunk = 2 * (grp16 & 1) + ((i16 & 3) >> 1), vbyte = 8 * (i16 & 1);
         auto seed = [&](int sb, f32x16& acc) {
           if (bias_h) {
 #pragma unroll
@@ -428,31 +484,14 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
         // instructions that do not depend on it:
         //   S,dP(0) | S,dP(1) + pointwise(0) | outputs(0) + pointwise(1) | outputs(1)
         // outputs = dQ^T += K^T dS^T (dQ pass) or dK^T += Q^T dS, dV^T += dO^T P (dK/dV pass).
-        typedef __attribute__((address_space(3))) short4v* lds_s4;
-        static_assert(C::kSwz0 && C::kSwz1 && C::STRIDE0 == C::STRIDE1, "both tiles share one layout here");
+        static_assert(C::kDma, "256-byte-row tiles only");
         const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
-        const int vchunk = 2 * (grp16 & 1) + ((i16 & 3) >> 1), vbyte = 8 * (i16 & 1);
-        // LDS addresses are formed next to each read with one XOR instead of being kept as loop invariants
-        // (one register per k-step / feature block otherwise).  For tile row r = 32*sb + l32 the swizzle is a
-        // lane constant z, and chunk 2*ks+hf lands at byte 256*r + 16*((2*ks+hf)^z) = 8192*sb + (kb ^ 32*ks).
-        // For the transpose reads (row R + 4*hf + i16/4 + 8*hi, R a multiple of 16, chunk 4*ob + vchunk)
-        // z = 4*(i16/4) + hf + 2*hi and the byte is 256*R + 2048*hi + (tb ^ (64*ob | 32*hi)).
-        const int zl = 4 * (l32 & 3) + ((l32 >> 2) & 3);
-        int kb = stage * C::STAGE_BYTES + l32 * 256 + ((hf ^ (zl & 1)) << 4) + ((zl >> 1) << 5);
-        int tb = stage * C::STAGE_BYTES + (4 * hf + (i16 >> 2)) * 256 + ((i16 >> 2) << 6) + ((vchunk ^ hf) << 4) + vbyte;
-        asm volatile("" : "+v"(kb), "+v"(tb));
         // score fragment n: tensor n%2 (S then dP), sub-block n/16, k-step (n/2)%8
-        auto rowfrag = [&](int n) -> bf16x8 {
-          return *(const bf16x8*)(smem + (kb ^ (((n >> 1) & 7) << 5)) + (n >> 4) * 8192 + (n & 1) * C::TILE0);
-        };
+        auto rowfrag = [&](int n) -> bf16x8 { return rowfrag_at(n & 1, n >> 4, (n >> 1) & 7); };
         // output fragment n: sub-block n / (8*NOUT), then (k-step, feature block) major, output minor
         auto trfrag = [&](int n) -> bf16x8 {
-          const int sb = n / (8 * C::NOUT), r = n % (8 * C::NOUT), step = r / C::NOUT, o = r % C::NOUT;
-          const int ks2 = step / C::OB, ob = step % C::OB;
-          const int roff = (sb * 32 + ks2 * 16) * 256 + o * C::TILE0;
-          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (tb ^ (ob << 6)) + roff));
-          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (tb ^ ((ob << 6) | 32)) + roff + 2048));
-          return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          const int r = n % (8 * C::NOUT), step = r / C::NOUT;
+          return trfrag_at(r % C::NOUT, n / (8 * C::NOUT), step / C::OB, step % C::OB);
         };
         f32x16 sv[2], dp[2];
         uint32_t pds[2][8], pp[2][8];
@@ -544,20 +583,25 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
         }
         if constexpr (C::kBf16) {
           // A-operand fragments are fetched one k-step ahead of the product that consumes them
-          bf16x8 f1[2][SBG], f2[2][SBG];
+          bf16x8 f1[2][SBG], f2[2][SBG], fs[2];
+          // stationary operand 1 when it lives in LDS: B fragment of this wave's row x
+          auto statfrag = [&](int ks) -> bf16x8 {
+            return *(const bf16x8*)(smem + ((kb - stage * C::STAGE_BYTES) ^ (ks << 5)) + C::STAT_BASE + wave * 8192);
+          };
+          if constexpr (C::kStatLds) fs[0] = statfrag(0);
 #pragma unroll
           for (int u = 0; u < SBG; ++u) {
-            f1[0][u] = *(const bf16x8*)(y1s + lds_off<C, 0>((sg + u) * 32 + l32, hf));
-            if (MODE != kFwd) f2[0][u] = *(const bf16x8*)(y2s + lds_off<C, 1>((sg + u) * 32 + l32, hf));
+            f1[0][u] = rowfrag_at(0, sg + u, 0);
+            if (MODE != kFwd) f2[0][u] = rowfrag_at(1, sg + u, 0);
           }
 #pragma unroll
           for (int ks = 0; ks < C::KS; ++ks) {
             if (ks + 1 < C::KS) {
+              if constexpr (C::kStatLds) fs[(ks + 1) & 1] = statfrag(ks + 1);
 #pragma unroll
               for (int u = 0; u < SBG; ++u) {
-                f1[(ks + 1) & 1][u] = *(const bf16x8*)(y1s + lds_off<C, 0>((sg + u) * 32 + l32, 2 * (ks + 1) + hf));
-                if (MODE != kFwd)
-                  f2[(ks + 1) & 1][u] = *(const bf16x8*)(y2s + lds_off<C, 1>((sg + u) * 32 + l32, 2 * (ks + 1) + hf));
+                f1[(ks + 1) & 1][u] = rowfrag_at(0, sg + u, ks + 1);
+                if (MODE != kFwd) f2[(ks + 1) & 1][u] = rowfrag_at(1, sg + u, ks + 1);
               }
             }
             if constexpr (C::KS % C::CPT == 0) {
@@ -569,8 +613,10 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
 #pragma unroll
             for (int u = 0; u < SBG; ++u) {
               sc1[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[ks & 1][u], res[0][ks], sc1[u], 0, 0, 0);
-              if constexpr (MODE != kFwd)
-                sc2[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[ks & 1][u], res[1][ks], sc2[u], 0, 0, 0);
+              if constexpr (MODE != kFwd) {
+                if constexpr (C::kStatLds) sc2[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[ks & 1][u], fs[ks & 1], sc2[u], 0, 0, 0);
+                else sc2[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[ks & 1][u], res[1][ks], sc2[u], 0, 0, 0);
+              }
             }
           }
         } else {
@@ -630,21 +676,11 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
           // transpose load: within a group of 16 lanes, lane 4r+c supplies the address of 4 features
           // (4c..4c+3) of streamed row r and lane i receives feature i of rows 0..3.  The 8 k-slots of
           // this lane in k-step ks2 are streamed rows ks2*16 + 4*hf + {0..3} and + 8 + {0..3}.
-          typedef __attribute__((address_space(3))) short4v* lds_s4;
-          const unsigned char* src0 = (MODE == kFwd) ? y2s : y1s;        // V (forward), K (dQ), Q (dK)
-          const int tchunk = 2 * (grp16 & 1) + ((i16 & 3) >> 1), tbyte = 8 * (i16 & 1);
           constexpr int NSTEP = SBG * 2 * C::OB;                          // (sub-block, k-step, feature block)
-          auto fetch = [&](int step, const unsigned char* src, auto tensor) -> bf16x8 {
-            constexpr int TS = decltype(tensor)::value;
-            const int u = step / (2 * C::OB), ks2 = (step / C::OB) & 1, ob = step % C::OB;
-            const int trow = (sg + u) * 32 + ks2 * 16 + 4 * hf + (i16 >> 2);
-            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(src + lds_off<C, TS>(trow, 4 * ob + tchunk) + tbyte));
-            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(src + lds_off<C, TS>(trow + 8, 4 * ob + tchunk) + tbyte));
-            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          constexpr int TSRC = (MODE == kFwd) ? 1 : 0;                    // V (forward), K (dQ), Q (dK)
+          auto fetch = [&](int step, int tensor) -> bf16x8 {
+            return trfrag_at(tensor, sg + step / (2 * C::OB), (step / C::OB) & 1, step % C::OB);
           };
-          using T0 = std::integral_constant<int, 0>;
-          using T1 = std::integral_constant<int, 1>;
-          using TSRC = std::integral_constant<int, MODE == kFwd ? 1 : 0>;
           uint32_t pk1[SBG][8], pk2[SBG][8];
 #pragma unroll
           for (int u = 0; u < SBG; ++u)
@@ -654,13 +690,13 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
               if (MODE == kBwdDKDV) pk2[u][m] = pack_bf16x2(c2[u][2 * m], c2[u][2 * m + 1]);
             }
           bf16x8 a1[2], a2[2];
-          a1[0] = fetch(0, src0, TSRC{});
-          if (MODE == kBwdDKDV) a2[0] = fetch(0, y2s, T1{});
+          a1[0] = fetch(0, TSRC);
+          if (MODE == kBwdDKDV) a2[0] = fetch(0, 1);
 #pragma unroll
           for (int step = 0; step < NSTEP; ++step) {
             if (step + 1 < NSTEP) {
-              a1[(step + 1) & 1] = fetch(step + 1, src0, TSRC{});
-              if (MODE == kBwdDKDV) a2[(step + 1) & 1] = fetch(step + 1, y2s, T1{});
+              a1[(step + 1) & 1] = fetch(step + 1, TSRC);
+              if (MODE == kBwdDKDV) a2[(step + 1) & 1] = fetch(step + 1, 1);
             }
             __builtin_amdgcn_sched_barrier(0);
             const int u = step / (2 * C::OB), ks2 = (step / C::OB) & 1, ob = step % C::OB;
@@ -770,6 +806,7 @@ int fwd_block_rows(int dtype, int) { return 32 * (dtype == 0 ? kFwdWavesBf16 : k
 int dq_block_rows(int dtype, int) { return 32 * (dtype == 0 ? kDqWavesBf16 : kDqWavesFp32); }
 int dkv_block_rows(int dtype, int) { return 32 * (dtype == 0 ? kDkvWavesBf16 : kDkvWavesFp32); }
 int stream_tile_rows(int dtype, int) { return dtype == 0 ? 64 : 32; }
+int dkv_tile_rows(int dtype, int D) { return dtype == 0 ? (D == 128 ? 32 : 64) : 32; }
 
 hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream) {
   return dispatch<kFwd, kFwdWavesBf16, kFwdWavesFp32>(a, dtype, stream);
