@@ -136,7 +136,7 @@ int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, i
  * launch made by the entry points above is bracketed by HIP events on its stream (up to 16 launches
  * between two reads).  hstu_profile_read waits for those events and returns the number of entries
  * written: names[i] (static strings: "attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "gated_norm_fwd",
- * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_*", "bias_expand") and
+ * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_fwd", "schedule_bwd" [both backward lists, one launch], "bias_expand") and
  * ms[i] = elapsed milliseconds.  HOST arrays.  Not thread-safe; enable(1) creates the events once. */
 int hstu_profile_enable(int on);
 int hstu_profile_read(int max_entries, const char** names, float* ms);

@@ -223,17 +223,19 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
     ProfScope ps("bias_expand", stream);
     if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
+  {
+    ProfScope ps("schedule_bwd", stream);
+    const int rows[2] = {dq_block_rows(p->dtype, p->head_dim), dkv_block_rows(p->dtype, p->head_dim)};
+    const int cols[2] = {tile, dkv_tile_rows(p->dtype, p->head_dim)};
+    SchedHeader* const hd[2] = {(SchedHeader*)(ws + l.header[0]), (SchedHeader*)(ws + l.header[1])};
+    WorkItem* const it[2] = {(WorkItem*)(ws + l.items[0]), (WorkItem*)(ws + l.items[1])};
+    int32_t* const sb[2] = {(int32_t*)(ws + l.seq_base[0]), (int32_t*)(ws + l.seq_base[1])};
+    if (launch_schedule_pair(a, rows, cols, hd, it, sb, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  }
   for (int s = 0; s < 2; ++s) {                          // s = 0: dQ pass (query blocks), s = 1: dK/dV pass (key blocks)
     a.max_items = l.max_items[s];
     a.header = (const SchedHeader*)(ws + l.header[s]);
     a.items = (const WorkItem*)(ws + l.items[s]);
-    const int rows = s == 0 ? dq_block_rows(p->dtype, p->head_dim) : dkv_block_rows(p->dtype, p->head_dim);
-    {
-      ProfScope ps(s == 0 ? "schedule_dq" : "schedule_dkdv", stream);
-      if (launch_schedule(a, rows, s == 1 ? dkv_tile_rows(p->dtype, p->head_dim) : tile, s == 1, (SchedHeader*)(ws + l.header[s]), (WorkItem*)(ws + l.items[s]),
-                          (int32_t*)(ws + l.seq_base[s]), stream) != hipSuccess)
-        return HSTU_ERR_LAUNCH;
-    }
     ProfScope ps(s == 0 ? "attn_bwd_dq" : "attn_bwd_dkdv", stream);
     const hipError_t e = s == 0 ? launch_attn_bwd_dq(a, p->dtype, stream) : launch_attn_bwd_dkdv(a, p->dtype, stream);
     if (e != hipSuccess) return HSTU_ERR_LAUNCH;

@@ -40,6 +40,9 @@ struct AttnArgs {
 // key rows when `key_major` is set) against column tiles of `tile_cols`.
 hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, bool key_major, SchedHeader* header,
                            WorkItem* items, int32_t* seq_base, hipStream_t stream);
+// The two lists of the backward pass in one launch: [0] query blocks (dQ pass), [1] key blocks (dK/dV pass).
+hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
+                                WorkItem* const items[2], int32_t* const seq_base[2], hipStream_t stream);
 hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
                               hipStream_t stream);
 
