@@ -79,3 +79,27 @@ def test_flop_accounting_matches_oracle_pair_count():
     from paper_2602_16986_amd import workloads as wl
     w = wl.config("C1")
     assert flops.attention_flops(w)["pairs"] == 62278
+
+
+def test_workspace_query_rejects_descriptions_the_kernels_cannot_address():
+    """hstu_attn_workspace_bytes returns 0 for an invalid description (no GPU call involved): the kernels
+    address a tile row as sequence base + 32-bit byte offset built from a 24-bit row and a 24-bit stride."""
+    from paper_2602_16986_amd import binding as hb
+    lib = hb._lib
+
+    def ws(**over):
+        p = hb.HstuAttnParams()
+        p.batch, p.num_heads, p.head_dim, p.total_tokens, p.max_seqlen, p.dtype = 2, 4, 128, 1000, 600, 0
+        p.row_stride_q = p.row_stride_k = p.row_stride_v = p.row_stride_o = 4 * 128
+        p.seq_offsets = 256                      # any non-null value: never dereferenced by the size query
+        p.local_window, p.global_prefix, p.alpha, p.inv_n = -1, 0, 1.0, 1.0
+        for k, v in over.items():
+            setattr(p, k, v)
+        return int(lib.hstu_attn_workspace_bytes(ctypes.byref(p), 0))
+
+    assert ws() > 0
+    assert ws(max_seqlen=1 << 24) == 0                       # row index must fit 24 bits
+    assert ws(row_stride_k=1 << 23) == 0                     # 2^23 bf16 elements = 16 MiB per row
+    assert ws(max_seqlen=1 << 20, row_stride_v=4096) == 0    # 2^20 rows x 8 KiB >= 4 GiB
+    assert ws(row_stride_q=4 * 128 + 4) == 0                 # rows must start on 16-byte boundaries
+    assert ws(head_dim=96) == 0
