@@ -92,7 +92,9 @@ typedef struct hstu_attn_params {
 /* Bytes of device scratch (256-byte aligned) that hstu_attn_fwd (for_backward = 0)
  * or hstu_attn_bwd (for_backward != 0) needs for this problem.  Depends only on
  * batch, num_heads, head_dim, total_tokens, max_seqlen and dtype.  Returns 0 for an
- * invalid description (the compute call then reports the error). */
+ * invalid description (the compute call then reports the error).  The backward figure
+ * includes fp32 partial-sum slots for key blocks that the scheduler cuts along the query
+ * axis (at most 768 x 2 x 128 x head_dim floats, about 100 MB at head_dim 128). */
 size_t hstu_attn_workspace_bytes(const hstu_attn_params* p, int for_backward);
 
 /* Paper Eq. 3, forward (attention_forward of the appendix pseudocode).
@@ -103,7 +105,8 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
 
 /* Backward of Eq. 3 (attention_backward(dattn, q, k, v) -> dq, dk, dv): the scores are
  * recomputed from q, k; nothing saved by the forward is needed.  dout uses row_stride_o,
- * dq/dk/dv use the strides of q/k/v.  The bias table receives no gradient. */
+ * dq/dk/dv use the strides of q/k/v.  The bias table receives no gradient.  Deterministic:
+ * no atomics; partial sums of cut key blocks are added in a fixed order. */
 int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, const void* dout,
                   void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
 

@@ -17,9 +17,16 @@ inline int64_t max_items_for(const hstu_attn_params* p, int block_rows) {
 }
 
 struct Layout {           // byte offsets inside a workspace
-  size_t header[2], items[2], seq_base[2], bias, total;
+  size_t header[2], items[2], seq_base[2], bias, splits, partial, total;
   int max_items[2];
+  int slot_cap;           // partial-sum slots of the dK/dV pass (key blocks cut along the query axis)
 };
+
+// Slots for the pieces of cut key blocks: at most 768 (about 1.5 per workgroup slot of the chip), never more than
+// twice the number of key blocks, none without a mask that can make a key block long (dense causal and local-only
+// masks never have one block much longer than the rest of its sequence... they may still be cut when sequences differ
+// a lot in length, which the same bound covers).
+inline int slot_cap_for(int max_items) { return max_items < 384 ? 2 * max_items : 768; }
 
 // One schedule for the forward; two (dQ pass, dK/dV pass) for the backward.
 Layout make_layout(const hstu_attn_params* p, int for_backward) {
@@ -30,12 +37,21 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
     const int rows = !for_backward ? fwd_block_rows(p->dtype, p->head_dim)
                                    : (s == 0 ? dq_block_rows(p->dtype, p->head_dim) : dkv_block_rows(p->dtype, p->head_dim));
     l.max_items[s] = (int)max_items_for(p, rows);
+    if (for_backward && s == 1) {                      // the dK/dV list also holds the pieces of cut key blocks
+      l.slot_cap = slot_cap_for(l.max_items[s]);
+      l.max_items[s] += l.slot_cap;
+    }
     l.header[s] = off; off += kAlign;
     l.items[s] = off; off += align_up((size_t)l.max_items[s] * sizeof(WorkItem));
     l.seq_base[s] = off; off += align_up(((size_t)p->batch + 1) * sizeof(int32_t));
   }
   l.bias = off;
   off += align_up((size_t)p->num_heads * ((size_t)p->max_seqlen + 1) * sizeof(float));
+  if (for_backward) {
+    l.splits = off; off += align_up((size_t)(l.slot_cap / 2 + 1) * sizeof(SplitItem));
+    l.partial = off;
+    off += align_up((size_t)l.slot_cap * 2 * dkv_block_rows(p->dtype, p->head_dim) * p->head_dim * sizeof(float));
+  }
   l.total = off;
   return l;
 }
@@ -230,15 +246,19 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
     SchedHeader* const hd[2] = {(SchedHeader*)(ws + l.header[0]), (SchedHeader*)(ws + l.header[1])};
     WorkItem* const it[2] = {(WorkItem*)(ws + l.items[0]), (WorkItem*)(ws + l.items[1])};
     int32_t* const sb[2] = {(int32_t*)(ws + l.seq_base[0]), (int32_t*)(ws + l.seq_base[1])};
-    if (launch_schedule_pair(a, rows, cols, hd, it, sb, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    if (launch_schedule_pair(a, rows, cols, hd, it, sb, (SplitItem*)(ws + l.splits), l.slot_cap, stream) != hipSuccess)
+      return HSTU_ERR_LAUNCH;
   }
   for (int s = 0; s < 2; ++s) {                          // s = 0: dQ pass (query blocks), s = 1: dK/dV pass (key blocks)
     a.max_items = l.max_items[s];
     a.header = (const SchedHeader*)(ws + l.header[s]);
     a.items = (const WorkItem*)(ws + l.items[s]);
+    a.partial = (float*)(ws + l.partial);
+    a.splits = (const SplitItem*)(ws + l.splits);
     ProfScope ps(s == 0 ? "attn_bwd_dq" : "attn_bwd_dkdv", stream);
     const hipError_t e = s == 0 ? launch_attn_bwd_dq(a, p->dtype, stream) : launch_attn_bwd_dkdv(a, p->dtype, stream);
     if (e != hipSuccess) return HSTU_ERR_LAUNCH;
+    if (s == 1 && launch_dkdv_combine(a, p->dtype, l.slot_cap / 2, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   return HSTU_OK;
 }

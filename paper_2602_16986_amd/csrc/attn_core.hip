@@ -123,6 +123,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
   if (pos >= a.header->count) return;
   const WorkItem item = a.items[pos];
   const int b = item.b, xb = item.rb_h >> 8, h = item.rb_h & 255;
+  const int t_begin = item.t0;
   const int seq0 = a.offsets[b];
   const int L = a.offsets[b + 1] - seq0;
   const SeqGeom g = {L, L - (a.num_targets ? a.num_targets[b] : 0), a.K1, a.K2};
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
 
   const int xlast = min(x0 + C::BX, L) - 1;
   const TileRanges tr = (MODE == kBwdDKDV) ? row_tile_ranges(g, x0, xlast, C::BN) : tile_ranges(g, x0, xlast, C::BN);
-  const int ntiles = tr.count();
+  const int ntiles = min(tr.count(), item.t1);             // this item's share of the block's tile list is [t_begin, ntiles)
   const float* bias_h = a.bias ? a.bias + (int64_t)h * a.bias_stride : nullptr;
   const bool unit_alpha = a.alpha == 1.0f;
   // this lane's start inside the bias strip: copy c = s0 mod 4 makes its 4-entry reads 16-byte aligned
@@ -328,15 +329,15 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
       dma16(tile_rsrc(R2, rowb, x0 + 4 * rg), voff, dst);
     }
   }
-  if (ntiles > 0) gload(tr.at(0), 0);
+  if (t_begin < ntiles) gload(tr.at(t_begin), 0);
   lstore(0);
   __syncthreads();
 
   constexpr int NSB = C::BN / 32;                     // 32-row sub-blocks of a streamed tile
   constexpr int SBG = (MODE == kFwd && NSB >= 2) ? 2 : 1;   // sub-blocks whose products are interleaved
-  for (int t = 0; t < ntiles; ++t) {
+  for (int t = t_begin; t < ntiles; ++t) {
     const int yt = tr.at(t);
-    const int stage = t & 1;
+    const int stage = (t - t_begin) & 1;
     const bool has_next = t + 1 < ntiles;
     const int yt_next = has_next ? tr.at(t + 1) : 0;
     const unsigned char* y1s = smem + stage * C::STAGE_BYTES;
@@ -735,6 +736,21 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
   }
 
   // ---- epilogue: scale once, convert, store.  Lane x holds features ob*32 + 8*(r/4) + 4*hf + r%4.
+  if constexpr (MODE == kBwdDKDV) {
+    if (item.slot >= 0) {
+      // a piece of a cut key block: raw fp32 sums go to its slot [dK, dV][block row][D]; dkdv_combine_kernel finishes
+      float* dst = a.partial + (((int64_t)item.slot * 2) * C::BX + (wave * 32 + l32)) * D;
+#pragma unroll
+      for (int o = 0; o < 2; ++o)
+#pragma unroll
+        for (int ob = 0; ob < C::OB; ++ob)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4)
+            *(f32x4*)(dst + (int64_t)o * C::BX * D + ob * 32 + 8 * q4 + 4 * hf) =
+                (f32x4){out[o][ob][4 * q4 + 0], out[o][ob][4 * q4 + 1], out[o][ob][4 * q4 + 2], out[o][ob][4 * q4 + 3]};
+      return;
+    }
+  }
   if (!x_ok) return;
 #pragma unroll
   for (int o = 0; o < C::NOUT; ++o) {
@@ -759,6 +775,32 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
           *(f32x4*)(dst + f) = (f32x4){v0, v1, v2, v3};
         }
       }
+  }
+}
+
+// Adds the partial sums of one cut key block in piece order (fixed order: deterministic), applies the
+// output scale and writes dK and dV rows.  Grid: (possible cut blocks, 8); block (b, rb, h) rows split 8 ways.
+template <typename E, int D>
+__global__ __launch_bounds__(256) void dkdv_combine_kernel(const AttnArgs a, int block_rows) {
+  const int si = blockIdx.x;
+  if (si >= a.header->splits) return;
+  const SplitItem it = a.splits[si];
+  const int seq0 = a.offsets[it.b], L = a.offsets[it.b + 1] - seq0;
+  const int xb = it.rb_h >> 8, h = it.rb_h & 255;
+  constexpr int VPR = D / 4;                                           // float4 per row
+  const int rows_here = block_rows / 8;
+  for (int i = threadIdx.x; i < 2 * rows_here * VPR; i += 256) {
+    const int o = i / (rows_here * VPR), r = blockIdx.y * rows_here + (i / VPR) % rows_here, c4 = i % VPR;
+    const int x = xb * block_rows + r;
+    if (x >= L) continue;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int pc = 0; pc < it.pieces; ++pc)
+      acc += *(const f32x4*)(a.partial + ((((int64_t)(it.first_slot + pc) * 2 + o) * block_rows + r) * D) + 4 * c4);
+    const float scale = o == 0 ? a.inv_n * a.alpha : a.inv_n * kLn2;
+    acc *= scale;
+    E* dst = (E*)(o == 0 ? a.dk : a.dv) + (int64_t)(seq0 + x) * (o == 0 ? a.sk : a.sv) + (int64_t)h * D + 4 * c4;
+    if constexpr (sizeof(E) == 2) *(u32x2*)dst = (u32x2){pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
+    else *(f32x4*)dst = acc;
   }
 }
 
@@ -816,6 +858,28 @@ hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream) 
 }
 hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream) {
   return dispatch<kBwdDKDV, kDkvWavesBf16, kDkvWavesFp32>(a, dtype, stream);
+}
+
+hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream) {
+  if (max_splits <= 0) return hipSuccess;
+  const int rows = dkv_block_rows(dtype, a.D);
+  const dim3 grid(max_splits, 8), block(256);
+  if (dtype == 0) {
+    switch (a.D) {
+      case 32: hipLaunchKernelGGL((dkdv_combine_kernel<__bf16, 32>), grid, block, 0, stream, a, rows); break;
+      case 64: hipLaunchKernelGGL((dkdv_combine_kernel<__bf16, 64>), grid, block, 0, stream, a, rows); break;
+      case 128: hipLaunchKernelGGL((dkdv_combine_kernel<__bf16, 128>), grid, block, 0, stream, a, rows); break;
+      default: return hipErrorInvalidValue;
+    }
+  } else {
+    switch (a.D) {
+      case 32: hipLaunchKernelGGL((dkdv_combine_kernel<float, 32>), grid, block, 0, stream, a, rows); break;
+      case 64: hipLaunchKernelGGL((dkdv_combine_kernel<float, 64>), grid, block, 0, stream, a, rows); break;
+      case 128: hipLaunchKernelGGL((dkdv_combine_kernel<float, 128>), grid, block, 0, stream, a, rows); break;
+      default: return hipErrorInvalidValue;
+    }
+  }
+  return hipGetLastError();
 }
 
 }  // namespace hstu

@@ -7,15 +7,24 @@ namespace hstu {
 
 // First 256 bytes of every attention workspace.
 struct SchedHeader {
-  int32_t count;          // scheduled work items (row block x head)
-  int32_t pad;
+  int32_t count;          // scheduled work items (row block x head, or pieces of one)
+  int32_t splits;         // row blocks that were cut into pieces (entries of the SplitItem list)
   int64_t tiles;          // scheduled (row block, column block) tiles, all heads
   int64_t dense_tiles;    // tiles of the full L x L grids, all heads
+  int32_t chunk_tiles;    // piece size used for the cut blocks
+  int32_t pad;
 };
 
 struct WorkItem {
   int32_t b;              // sequence
   int32_t rb_h;           // (block index << 8) | head
+  int32_t t0, t1;         // positions [t0, min(t1, tiles of the block)) of the block's tile list
+  int32_t slot;           // partial-sum slot of a piece, -1: the item writes its block's output itself
+  int32_t pad;
+};
+
+struct SplitItem {        // a row block whose pieces left partial sums in slots [first_slot, first_slot + pieces)
+  int32_t b, rb_h, first_slot, pieces;
 };
 
 // Everything a kernel needs to know about the attention problem.
@@ -33,6 +42,8 @@ struct AttnArgs {
   const SchedHeader* header;
   const WorkItem* items;
   int32_t max_items;
+  float* partial;                   // dK/dV pass: fp32 partial sums [slot][dK, dV][block row][D] of cut key blocks
+  const SplitItem* splits;
 };
 
 // schedule.hip
@@ -41,8 +52,10 @@ struct AttnArgs {
 hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, bool key_major, SchedHeader* header,
                            WorkItem* items, int32_t* seq_base, hipStream_t stream);
 // The two lists of the backward pass in one launch: [0] query blocks (dQ pass), [1] key blocks (dK/dV pass).
+// `splits` / `slot_cap`: list of cut key blocks and number of partial-sum slots available to the dK/dV list.
 hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
-                                WorkItem* const items[2], int32_t* const seq_base[2], hipStream_t stream);
+                                WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* splits, int slot_cap,
+                                hipStream_t stream);
 hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
                               hipStream_t stream);
 
@@ -55,6 +68,8 @@ int dkv_tile_rows(int dtype, int D);      // ... in the dK/dV pass
 hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream);
+// adds the partial sums of every cut key block in piece order, scales, converts and writes dK, dV
+hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream);
 
 // gated_norm.hip
 int gated_norm_bwd_blocks(int64_t T);

@@ -4,11 +4,11 @@
 // ordered list of work items (sequence, block of rows, head).  Fully masked column tiles
 // are never visited: every kernel enumerates the visible tiles of its block with
 // tile_ranges()/row_tile_ranges(), and the scheduler uses the same functions to price
-// each block so that expensive blocks start first (longest-processing-time order) while
-// neighbouring blocks of one (sequence, head) stay adjacent in the list; the attention
-// kernels then map list positions to accelerator dies so that such neighbours share one
-// die's L2 for their K/V stream.  Semi-local attention costs O((K1+K2) L) only because
-// of this skipping (paper Section 4.2.1).
+// each block so that expensive blocks start first (longest-processing-time order).  In the
+// key-major list of the dK/dV pass a block far longer than the average (the key blocks of a
+// global prefix, which every query of the sequence sees) is cut into pieces along the query
+// axis; the pieces write partial sums that a small kernel adds up in a fixed order.
+// Semi-local attention costs O((K1+K2) L) only because of the skipping (paper Section 4.2.1).
 #include "hstu_common.h"
 #include "hstu_kernels.h"
 
@@ -16,15 +16,38 @@ namespace hstu {
 
 constexpr int kSchedThreads = 1024;
 constexpr int kSortMax = 8192;       // lists up to this size are sorted by cost in LDS
-constexpr int kSeqCache = 2048;      // batches up to this size keep their block prefix sums and lengths in LDS
+constexpr int kSeqCache = 1024;      // batches up to this size keep their block prefix sums and lengths in LDS
+constexpr int kItemsPerThread = kSortMax / kSchedThreads;
+constexpr int kMinChunk = 8;         // a long key block is cut into pieces of at least this many tiles ...
+constexpr int kTargetChunks = 2048;  // ... and of about 1/2048 of all scheduled tiles (4 per workgroup slot of the chip)
 
 // One workgroup builds one list; the backward pass launches two (dQ blocks and dK/dV blocks) side by side.
 struct SchedJob {
   int block_rows, tile_cols, key_major;
+  int slot_cap;            // > 0: blocks much longer than the average may be cut along the streamed axis
   SchedHeader* header;
   WorkItem* items;
   int32_t* seq_base;
+  SplitItem* splits;
 };
+
+// Exclusive scan of one 64-bit value per thread over the workgroup (three packed counters); returns the
+// exclusive prefix and writes the grand total.
+__device__ unsigned long long block_scan64(unsigned long long v, unsigned long long* lds, unsigned long long& total) {
+  const int tid = threadIdx.x;
+  lds[tid] = v;
+  __syncthreads();
+  for (int off = 1; off < kSchedThreads; off <<= 1) {
+    const unsigned long long u = tid >= off ? lds[tid - off] : 0ull;
+    __syncthreads();
+    lds[tid] += u;
+    __syncthreads();
+  }
+  const unsigned long long incl = lds[tid];
+  total = lds[kSchedThreads - 1];
+  __syncthreads();
+  return incl - v;
+}
 
 __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* __restrict__ offsets,
                                                                  const int32_t* __restrict__ num_targets, int B, int H,
@@ -35,8 +58,11 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   WorkItem* items = job.items;
   int32_t* seq_base = job.seq_base;
   __shared__ int32_t scan[kSchedThreads];
-  __shared__ uint32_t keys[kSortMax];
-  __shared__ WorkItem staged[kSortMax];                  // items in natural order, permuted by the sort at the end
+  __shared__ unsigned long long scan64[kSchedThreads];
+  __shared__ uint32_t keys[kSortMax];                    // (inverted cost << 13) | entry
+  __shared__ uint32_t entry_item[kSortMax];              // entry -> item | (piece << 13)
+  __shared__ uint32_t cost_c[kSortMax];                  // item -> tiles
+  __shared__ uint16_t slot_c[kSortMax];                  // item -> first partial-sum slot, 0xFFFF = not cut
   __shared__ int32_t base_c[kSeqCache + 1], len_c[kSeqCache], hist_c[kSeqCache];
   const bool cached = B <= kSeqCache;                    // else the searches below read seq_base / offsets from global memory
   __shared__ int32_t carry_s;
@@ -81,41 +107,54 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   __syncthreads();
   const int total = blocks_per_head * H;                 // <= max_items by construction of the bound
 
-  // 2. natural order: sequence-major, then head, then block index descending.  Item idx -> (b, h, rb).
-  const bool sorted = total <= kSortMax;
-  // exact longest-first order measured best: the heaviest block is half of one compute unit's whole
-  // share on the 8k-16k workload, so any coarsening of the order shows up as tail imbalance
-  const int cost_quantum = 1;
-  unsigned long long my_tiles = 0, my_dense = 0;
-  for (int idx = tid; idx < total; idx += kSchedThreads) {
-    // find b with seq_base[b]*H <= idx < seq_base[b+1]*H
+  // natural order: sequence-major, then head, then block index descending.  Item idx -> (b, h, rb) and its tiles.
+  auto locate = [&](int idx, int& b, int& rb, int& h, int& cost, int& dense, bool want_cost) {
     int lo = 0, hi = B;                                  // invariant: seq_base[lo]*H <= idx < seq_base[hi]*H
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
       if ((long long)(cached ? base_c[mid] : seq_base[mid]) * H <= idx) lo = mid; else hi = mid;
     }
-    const int b = lo;
+    b = lo;
     const int base_b = cached ? base_c[b] : seq_base[b];
     const int nb = (cached ? base_c[b + 1] : seq_base[b + 1]) - base_b;
     const int local = idx - base_b * H;
-    const int h = local / nb;
-    const int rb = nb - 1 - (local % nb);
+    h = local / nb;
+    rb = nb - 1 - (local % nb);
+    if (!want_cost) return;
     const int L = cached ? len_c[b] : offsets[b + 1] - offsets[b];
     SeqGeom g = {L, cached ? hist_c[b] : L - (num_targets ? num_targets[b] : 0), K1, K2};
     const int r0 = rb * block_rows, r1 = min(r0 + block_rows, L) - 1;
     const TileRanges tr = key_major ? row_tile_ranges(g, r0, r1, tile_cols) : tile_ranges(g, r0, r1, tile_cols);
-    const int cost = tr.count();
-    my_tiles += cost;
-    my_dense += (L + tile_cols - 1) / tile_cols;
-    if (sorted) {
-      // ties keep the natural order: the heads of one (sequence, block) stay adjacent
-      const uint32_t cq = min((uint32_t)cost / (uint32_t)cost_quantum, 0x7FFFFu);
-      keys[idx] = ((0x7FFFFu - cq) << 13) | (uint32_t)idx;        // idx < 8192 = 2^13
-      staged[idx].b = b;
-      staged[idx].rb_h = (rb << 8) | h;
-    } else {
-      items[idx].b = b;
-      items[idx].rb_h = (rb << 8) | h;
+    cost = tr.count();
+    dense = (L + tile_cols - 1) / tile_cols;
+  };
+
+  // 2. price the items.  Sorted lists: thread tid owns the items [tid * ipt, (tid + 1) * ipt).
+  const bool sorted = total <= kSortMax;
+  const int ipt = (total + kSchedThreads - 1) / kSchedThreads;
+  unsigned long long my_tiles = 0, my_dense = 0;
+  int my_cost[kItemsPerThread];
+  if (sorted) {
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+      const int idx = tid * ipt + k;
+      my_cost[k] = 0;
+      if (k < ipt && idx < total) {
+        int b, rb, h, cost, dense;
+        locate(idx, b, rb, h, cost, dense, true);
+        my_cost[k] = cost;
+        cost_c[idx] = (uint32_t)cost;
+        my_tiles += cost;
+        my_dense += dense;
+      }
+    }
+  } else {
+    for (int idx = tid; idx < total; idx += kSchedThreads) {
+      int b, rb, h, cost, dense;
+      locate(idx, b, rb, h, cost, dense, true);
+      my_tiles += cost;
+      my_dense += dense;
+      items[idx] = WorkItem{b, (rb << 8) | h, 0, 0x7FFFFFFF, -1, 0};
     }
   }
   for (int off = 32; off > 0; off >>= 1) {                 // one LDS atomic per wave, not per thread
@@ -127,18 +166,70 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     atomicAdd(&dense_s, my_dense);
   }
   __syncthreads();
-  if (tid == 0) {
-    header->count = total;
-    header->pad = 0;
-    header->tiles = (int64_t)tiles_s;
-    header->dense_tiles = (int64_t)dense_s;
+  const unsigned long long all_tiles = tiles_s;
+  if (!sorted) {
+    if (tid == 0) *header = SchedHeader{total, 0, (int64_t)all_tiles, (int64_t)dense_s, 0, 0};
+    return;
   }
-  if (!sorted) return;
 
-  // 3. bitonic sort of the keys (ascending = most expensive first), padded to a power of two
+  // 3. Cut items that are much longer than a workgroup slot's share into pieces of `chunk` tiles (key-major
+  // lists only: the few key blocks of a global prefix are seen by every query of their sequence).  Each piece
+  // becomes an entry of the list and accumulates into a partial-sum slot of its own.  The piece size doubles until
+  // the slots and the list fit.  Packed counters: entries | slots << 20 | cut items << 40.
+  int chunk = (int)min((unsigned long long)0x3FFFFFFF, max((unsigned long long)kMinChunk, (all_tiles + kTargetChunks - 1) / kTargetChunks));
+  unsigned long long excl = (unsigned long long)min(tid * ipt, total), sum = (unsigned long long)total;
+  while (job.slot_cap > 0) {                               // no slots: one entry per item, in natural order
+    unsigned long long mine = 0;
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+      const int idx = tid * ipt + k;
+      if (k < ipt && idx < total) {
+        const int cost = my_cost[k];
+        const bool cut = job.slot_cap > 0 && cost > 2 * chunk;
+        const unsigned long long pieces = cut ? (unsigned long long)((cost + chunk - 1) / chunk) : 1ull;
+        mine += pieces | (cut ? (pieces << 20) | (1ull << 40) : 0ull);
+      }
+    }
+    excl = block_scan64(mine, scan64, sum);
+    const int entries = (int)(sum & 0xFFFFF), slots = (int)((sum >> 20) & 0xFFFFF);
+    if (entries <= kSortMax && slots <= job.slot_cap) break;   // uniform: every thread sees the same totals
+    chunk *= 2;                                                // ends: with no item cut, entries = total <= kSortMax
+  }
+  const int entries = (int)(sum & 0xFFFFF), nsplit = (int)(sum >> 40);
+  if (tid == 0) *header = SchedHeader{entries, nsplit, (int64_t)all_tiles, (int64_t)dense_s, chunk, 0};
+  {
+    int e = (int)(excl & 0xFFFFF), slot = (int)((excl >> 20) & 0xFFFFF), rank = (int)(excl >> 40);
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+      const int idx = tid * ipt + k;
+      if (k < ipt && idx < total) {
+        const int cost = my_cost[k];
+        const bool cut = job.slot_cap > 0 && cost > 2 * chunk;
+        const int pieces = cut ? (cost + chunk - 1) / chunk : 1;
+        slot_c[idx] = cut ? (uint16_t)slot : (uint16_t)0xFFFF;
+        for (int c = 0; c < pieces; ++c) {
+          // ties keep the natural order: the heads of one (sequence, block) stay adjacent
+          const uint32_t pc = (uint32_t)min(cut ? min(chunk, cost - c * chunk) : cost, 0x7FFFF);
+          keys[e + c] = ((0x7FFFFu - pc) << 13) | (uint32_t)(e + c);      // entry < 8192 = 2^13
+          entry_item[e + c] = (uint32_t)idx | ((uint32_t)c << 13);
+        }
+        if (cut) {
+          int b, rb, h, cost2, dense;
+          locate(idx, b, rb, h, cost2, dense, false);
+          job.splits[rank] = SplitItem{b, (rb << 8) | h, slot, pieces};
+          slot += pieces;
+          ++rank;
+        }
+        e += pieces;
+      }
+    }
+  }
+
+  // 4. bitonic sort of the keys (ascending = most expensive first), padded to a power of two
   int n2 = 1;
-  while (n2 < total) n2 <<= 1;
-  for (int idx = total + tid; idx < n2; idx += kSchedThreads) keys[idx] = 0xFFFFFFFFu;
+  while (n2 < entries) n2 <<= 1;
+  __syncthreads();
+  for (int idx = entries + tid; idx < n2; idx += kSchedThreads) keys[idx] = 0xFFFFFFFFu;
   __syncthreads();
   // Element i = tid + 1024*m is held by thread tid; compare-exchange partners at distance j < 64 are lanes of
   // the same wave, so those sub-stages run in registers with lane shuffles and need no barrier.
@@ -171,21 +262,30 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     }
     if (j > 0) wave_stages(k, j);
   }
-  for (int pos = tid; pos < total; pos += kSchedThreads) items[pos] = staged[keys[pos] & 0x1FFF];
+  for (int pos = tid; pos < entries; pos += kSchedThreads) {
+    const uint32_t ei = entry_item[keys[pos] & 0x1FFF];
+    const int idx = (int)(ei & 0x1FFF), c = (int)(ei >> 13);
+    const bool cut = slot_c[idx] != 0xFFFF;
+    int b, rb, h, cost = 0, dense;
+    locate(idx, b, rb, h, cost, dense, cut);
+    items[pos] = cut ? WorkItem{b, (rb << 8) | h, c * chunk, min((c + 1) * chunk, cost), (int)slot_c[idx] + c, 0}
+                     : WorkItem{b, (rb << 8) | h, 0, 0x7FFFFFFF, -1, 0};
+  }
 }
 
 hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, bool key_major, SchedHeader* header,
                            WorkItem* items, int32_t* seq_base, hipStream_t stream) {
-  const SchedJob job = {block_rows, tile_cols, key_major ? 1 : 0, header, items, seq_base};
+  const SchedJob job = {block_rows, tile_cols, key_major ? 1 : 0, 0, header, items, seq_base, nullptr};
   hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
                      a.K2, job, job);
   return hipGetLastError();
 }
 
 hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
-                                WorkItem* const items[2], int32_t* const seq_base[2], hipStream_t stream) {
-  const SchedJob j0 = {block_rows[0], tile_cols[0], 0, header[0], items[0], seq_base[0]};
-  const SchedJob j1 = {block_rows[1], tile_cols[1], 1, header[1], items[1], seq_base[1]};
+                                WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* splits, int slot_cap,
+                                hipStream_t stream) {
+  const SchedJob j0 = {block_rows[0], tile_cols[0], 0, 0, header[0], items[0], seq_base[0], nullptr};
+  const SchedJob j1 = {block_rows[1], tile_cols[1], 1, slot_cap, header[1], items[1], seq_base[1], splits};
   hipLaunchKernelGGL(schedule_kernel, dim3(2), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
                      a.K2, j0, j1);
   return hipGetLastError();
