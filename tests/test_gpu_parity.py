@@ -172,3 +172,26 @@ def test_layer_chain_small(hb):
     check("dQ", to_np(dw.dq), rq, 2e-2)
     check("dK", to_np(dw.dk), rk, 2e-2)
     check("dV", to_np(dw.dv), rv, 2e-2)
+
+
+@pytest.mark.parametrize("B,lo,hi,K1,K2", [
+    (24, 500, 1100, 64, 128),     # a few hundred global-prefix key blocks, each cut into 3-4 pieces
+    (96, 520, 700, 32, 128),      # more cut candidates than partial-sum slots: the piece size grows until they fit
+    (3, 2500, 4000, 96, 300),     # long pieces, ragged prefix (300 keys = 2.3 key blocks)
+])
+def test_backward_with_cut_key_blocks(hb, B, lo, hi, K1, K2):
+    """dK/dV of key blocks that the scheduler cuts along the query axis (keys of the global prefix are seen by
+    every query): pieces leave fp32 partial sums that a combine kernel adds up; compared with the oracle."""
+    rng = np.random.default_rng(B * 1000 + K2)
+    L = rng.integers(lo, hi + 1, size=B)
+    L[1] = 0                                              # an empty sequence in the middle of the list
+    w = wl.build(f"cut-B{B}", L, 2, 128, "bf16", rng=rng, K1=K1, K2=K2, backward=True)
+    run_case(w)
+
+
+def test_backward_cut_key_blocks_d64_and_fp32(hb):
+    rng = np.random.default_rng(77)
+    w = wl.build("cut-d64", rng.integers(900, 1500, size=4), 2, 64, "bf16", rng=rng, K1=40, K2=100, backward=True)
+    run_case(w)
+    w = wl.build("cut-fp32", rng.integers(600, 900, size=3), 2, 32, "fp32", rng=rng, K1=40, K2=100, backward=True)
+    run_case(w)
