@@ -43,23 +43,22 @@ struct Cfg {
   static constexpr int ROW_BYTES = D * (int)sizeof(E);
   // LDS tiles are read two ways: 16-byte reads with one streamed row per lane (score products)
   // and transpose reads that touch 4 consecutive rows x 64 bytes per 32 lanes (second products).
-  // A tile read only one way gets the row padding that makes that way conflict-free (16 bytes
-  // for row-per-lane reads, 64 for transpose reads) and plain base+offset addressing.  For 256-byte
-  // bf16 rows no padding serves both ways, so a tile read both ways is unpadded and stores the
-  // 16-byte chunks of row r at chunk ^ swz(r), swz(r) = 4*(r%4) + (r/4)%4: 16 consecutive rows then
-  // map one logical chunk to 16 different bank groups, and 4 consecutive rows map 4 consecutive
-  // chunks to 16 different ones.
   //   tensor 0 (Y1): K in the forward (rows only), K in the dQ pass and Q in the dK/dV pass (both ways)
   //   tensor 1 (Y2): V in the forward (transposed only), V in the dQ pass (rows only), dO in dK/dV (both)
+  // 256-byte bf16 rows are unpadded and store the 16-byte chunks of row r at chunk ^ swz(r),
+  // swz(r) = 4*(r%4) + (r/4)%4: 16 consecutive rows then map one logical chunk to 16 different bank
+  // groups, and 4 consecutive rows map 4 consecutive chunks to 16 different ones, so both ways of
+  // reading are conflict-free.  Such tiles travel from global memory straight into LDS (no register
+  // staging): a wave-level 16-byte load places its 64 lanes in 1 KB of consecutive LDS, and each lane
+  // applies the swizzle to its global address instead.  Narrower rows and fp32 are staged through
+  // registers into padded rows: the padding that makes the way(s) a tile is read conflict-free
+  // (16 bytes for row-per-lane reads, 64 for transpose reads, 80 for both).
   static constexpr bool kBoth0 = MODE != kFwd, kBoth1 = MODE == kBwdDKDV;
-  // 4-wave query-stationary workgroups run two per compute unit (two independent instruction streams
-  // per SIMD): 256 registers per lane and half of the 160 KB of LDS each.
-  static constexpr bool kTwoPerCu = kBf16 && NWAVES == 4 && (MODE != kBwdDKDV || kStatLds);
-  // 256-byte bf16 rows travel from global memory straight into LDS (no register staging): a wave-level
-  // 16-byte load places its 64 lanes in 1 KB of consecutive LDS, so those tiles are unpadded, and the
-  // swizzle (which each lane applies to its global address instead) serves both ways of reading them.
   static constexpr bool kDma = kBf16 && D == 128;
   static constexpr bool kSwz0 = kDma, kSwz1 = kDma;
+  // 4-wave bf16 workgroups run two per compute unit (two independent instruction streams per SIMD):
+  // 256 registers per lane and half of the 160 KB of LDS each.
+  static constexpr bool kTwoPerCu = kBf16 && NWAVES == 4 && (MODE != kBwdDKDV || kStatLds);
   static constexpr int PAD0 = !kBf16 ? 16 : (kSwz0 ? 0 : (kBoth0 ? 80 : 16));
   static constexpr int PAD1 = !kBf16 ? 16 : (kSwz1 ? 0 : (kBoth1 ? 80 : (MODE == kFwd ? 64 : 16)));
   static constexpr int STRIDE0 = ROW_BYTES + PAD0, STRIDE1 = ROW_BYTES + PAD1;   // LDS row strides, bytes
@@ -78,7 +77,6 @@ struct Cfg {
   // fetch 4 consecutive entries with one aligned 16-byte LDS read.
   // Copy length = 16 (mod 64) entries keeps the 16 reads of a quarter-wave on 16 different bank groups.
   static constexpr int SLEN = (BX + BN + 4 - 16 + 63) / 64 * 64 + 16;   // entries per copy
-  static constexpr bool kStripDma = true;                        // strip: direct-to-LDS runs, or one register-staged entry per lane
   static constexpr int STRIP_BYTES = 4 * SLEN * 4;
   static constexpr int STRIP_BASE = 2 * STAGE_BYTES;
   static constexpr int STAT_BASE = 2 * STAGE_BYTES + 2 * STRIP_BYTES;
@@ -201,7 +199,6 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
 
   // ---- staging of the streamed tiles: global -> LDS directly, or through registers
   u32x4 pre1[C::CPT], pre2[C::CPT];
-  float pre_bias = 0.f;
   const uint32_t rowb1 = (uint32_t)(sy1 * (int64_t)sizeof(E)), rowb2 = (uint32_t)(sy2 * (int64_t)sizeof(E));
   // Tile loads are raw buffer loads: the descriptor (uniform, built on the scalar unit) carries the
   // address of the piece's first row and the bytes left in the sequence from there, the lane supplies
@@ -263,7 +260,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
   // piece c of tile yt, bound for LDS stage `stage`
   typedef __attribute__((address_space(3))) void* lds_void;
   auto gload_piece = [&](int yt, int c, int stage) {
-    if (bias_h && C::kStripDma) {
+    if (bias_h) {
 #pragma unroll
       for (int j = 0; j < STRIP_J; ++j)
         if (j % C::CPT == c && NWAVES * j + wave < STRIP_RUNS) {
@@ -274,11 +271,6 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
           const uint32_t dst = (uint32_t)(uintptr_t)(lds_void)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES + 256 * (NWAVES * j + wave));
           dma4(bias_rs, voff, dst);
         }
-    }
-    if (bias_h && !C::kStripDma && c == 0) {
-      const int d0 = (MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) : x0 + (C::BX - 1) - yt * C::BN;
-      const int base = (MODE == kBwdDKDV) ? d0 + tid : d0 - tid;
-      pre_bias = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(__builtin_amdgcn_make_buffer_rsrc((void*)bias_h, 0, a.bias_stride * 4, 0x00020000), base * 4, 0, 0));
     }
     if constexpr (C::kDma) {
       const int rg = NWAVES * c + wave;
@@ -295,12 +287,6 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     for (int c = 0; c < C::CPT; ++c) gload_piece(yt, c, stage);
   };
   auto lstore = [&](int stage) {
-    if (bias_h && !C::kStripDma && tid < C::BX + C::BN - 1) {
-      float* strip = (float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES);
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-        if (tid - c >= 0) strip[c * C::SLEN + tid - c] = pre_bias;        // copy c holds strip[m + c] at m
-    }
     // this wave's direct-to-LDS pieces (strip runs, 256-byte-row tiles) have landed once its load counter
     // drains; the barrier that follows publishes them to the other waves
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
