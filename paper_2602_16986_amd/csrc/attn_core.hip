@@ -231,11 +231,12 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     strip_s4[j] = 4u * (uint32_t)(e % C::SLEN + e / C::SLEN);
     asm volatile("" : "+v"(strip_s4[j]));
   }
+  // raw buffer descriptor: 48-bit base, stride 0, bytes in range, 32-bit untyped data format
+  auto make_rsrc = [&](uint64_t addr, uint32_t bytes) -> i32x4 {
+    return (i32x4){(int)(uint32_t)addr, (int)(uint32_t)(addr >> 32), (int)bytes, 0x00020000};
+  };
   auto tile_rsrc = [&](const E* base, uint32_t rowb, int first_row) -> i32x4 {
-    const uint32_t left = (uint32_t)max(L - first_row, 0) * rowb;
-    const uint64_t addr = (uint64_t)(uintptr_t)base + (uint64_t)(uint32_t)first_row * rowb;
-    // raw buffer descriptor: 48-bit base, stride 0, bytes in range, 32-bit untyped data format
-    return (i32x4){(int)(uint32_t)addr, (int)((uint32_t)(addr >> 32) & 0xFFFFu), (int)left, 0x00020000};
+    return make_rsrc((uint64_t)(uintptr_t)base + (uint64_t)(uint32_t)first_row * rowb, (uint32_t)max(L - first_row, 0) * rowb);
   };
   // One 16-byte-per-lane load straight into LDS: lane l lands at LDS byte dst + 16 * l (dst uniform, passed
   // in M0).  Written as one opaque instruction group so that the compiler does not order the LDS reads of
@@ -249,42 +250,56 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
                  :: "s"(dst), "v"(voff), "s"(rs) : "memory", "m0");
   };
-  const uint64_t bias_addr = (uint64_t)(uintptr_t)bias_h;
-  const i32x4 bias_rs = {(int)(uint32_t)bias_addr, (int)((uint32_t)(bias_addr >> 32) & 0xFFFFu), a.bias_stride * 4, 0x00020000};
-  auto load16 = [&](const E* base, uint32_t rowb, int first_row, uint32_t voff) -> u32x4 {
-    const uint32_t left = (uint32_t)max(L - first_row, 0) * rowb;
-    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)((const unsigned char*)base + (uint64_t)(uint32_t)first_row * rowb), 0, (int)left, 0x00020000);
+  auto load16 = [&](uint64_t addr, uint32_t bytes, uint32_t voff) -> u32x4 {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)(uintptr_t)addr, 0, (int)bytes, 0x00020000);
     return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, 0, 0);
   };
-  // piece c of tile yt, bound for LDS stage `stage`
   typedef __attribute__((address_space(3))) void* lds_void;
-  auto gload_piece = [&](int yt, int c, int stage) {
+  // The tile to fetch next, as scalars set once per tile: address of this wave's first 4-row group in both
+  // tensors, rows left in the sequence from there, strip origin.  A tile that does not exist (end of the list)
+  // gets empty descriptors: its loads are still issued, read as zero and land in the stage nobody reads.
+  uint64_t nx_a1 = 0, nx_a2 = 0;
+  int nx_left = 0, nx_d0x4 = 0, nx_yt = 0;
+  uint32_t nx_bias_bytes = 0;
+  auto set_next = [&](int yt, bool valid) {
+    const int yrow = yt * C::BN + (C::kDma ? 4 * wave : 0);
+    nx_yt = yt;
+    nx_a1 = (uint64_t)(uintptr_t)Y1 + (uint64_t)(uint32_t)yrow * rowb1;
+    nx_a2 = (uint64_t)(uintptr_t)Y2 + (uint64_t)(uint32_t)yrow * rowb2;
+    nx_left = valid ? L - yrow : 0;
+    nx_d0x4 = 4 * ((MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) : x0 + (C::BX - 1) - yt * C::BN);
+    nx_bias_bytes = valid ? (uint32_t)a.bias_stride * 4u : 0u;
+  };
+  const uint64_t bias_addr = (uint64_t)(uintptr_t)bias_h;
+  // piece c of the next tile, bound for LDS stage `stage`
+  auto gload_piece = [&](int c, int stage) {
     if (bias_h) {
 #pragma unroll
       for (int j = 0; j < STRIP_J; ++j)
         if (j % C::CPT == c && NWAVES * j + wave < STRIP_RUNS) {
           // byte offset of table entry (distance of strip index s); entries outside [0, bias_stride) are
           // out of range of the descriptor and read as zero
-          const int d0 = (MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) : x0 + (C::BX - 1) - yt * C::BN;
-          const uint32_t voff = (MODE == kBwdDKDV) ? (uint32_t)(4 * d0) + strip_s4[j] : (uint32_t)(4 * d0) - strip_s4[j];
+          const uint32_t voff = (MODE == kBwdDKDV) ? (uint32_t)nx_d0x4 + strip_s4[j] : (uint32_t)nx_d0x4 - strip_s4[j];
           const uint32_t dst = (uint32_t)(uintptr_t)(lds_void)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES + 256 * (NWAVES * j + wave));
-          dma4(bias_rs, voff, dst);
+          dma4(make_rsrc(bias_addr, nx_bias_bytes), voff, dst);
         }
     }
     if constexpr (C::kDma) {
-      const int rg = NWAVES * c + wave;
-      const uint32_t dst = (uint32_t)(uintptr_t)(lds_void)(smem + stage * C::STAGE_BYTES + rg * 1024);
-      dma16(tile_rsrc(Y1, rowb1, yt * C::BN + 4 * rg), voff1, dst);
-      dma16(tile_rsrc(Y2, rowb2, yt * C::BN + 4 * rg), voff2, dst + C::TILE0);
+      const int dr = 4 * NWAVES * c;                                     // rows from this wave's group of piece 0 to that of piece c
+      const uint32_t left = (uint32_t)max(nx_left - dr, 0);
+      const uint32_t dst = (uint32_t)(uintptr_t)(lds_void)(smem + stage * C::STAGE_BYTES + (NWAVES * c + wave) * 1024);
+      dma16(make_rsrc(nx_a1 + (uint32_t)dr * rowb1, left * rowb1), voff1, dst);
+      dma16(make_rsrc(nx_a2 + (uint32_t)dr * rowb2, left * rowb2), voff2, dst + C::TILE0);
     } else if (C::CHUNKS % C::NT == 0 || tid < C::CHUNKS) {
-      pre1[c] = load16(Y1, rowb1, yt * C::BN + c * PIECE_ROWS, voff1);
-      pre2[c] = load16(Y2, rowb2, yt * C::BN + c * PIECE_ROWS, voff2);
+      const int dr = c * PIECE_ROWS;
+      const uint32_t left = (uint32_t)max(nx_left - dr, 0);
+      pre1[c] = load16(nx_a1 + (uint32_t)dr * rowb1, left * rowb1, voff1);
+      pre2[c] = load16(nx_a2 + (uint32_t)dr * rowb2, left * rowb2, voff2);
     }
   };
-  auto gload = [&](int yt, int stage) {
+  auto gload = [&](int stage) {
 #pragma unroll
-    for (int c = 0; c < C::CPT; ++c) gload_piece(yt, c, stage);
+    for (int c = 0; c < C::CPT; ++c) gload_piece(c, stage);
   };
   auto lstore = [&](int stage) {
     // this wave's direct-to-LDS pieces (strip runs, 256-byte-row tiles) have landed once its load counter
@@ -315,7 +330,8 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
       dma16(tile_rsrc(R2, rowb, x0 + 4 * rg), voff, dst);
     }
   }
-  if (t_begin < ntiles) gload(tr.at(t_begin), 0);
+  set_next(t_begin < ntiles ? tr.at(t_begin) : 0, t_begin < ntiles);
+  gload(0);
   lstore(0);
   __syncthreads();
 
@@ -325,7 +341,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     const int yt = tr.at(t);
     const int stage = (t - t_begin) & 1;
     const bool has_next = t + 1 < ntiles;
-    const int yt_next = has_next ? tr.at(t + 1) : 0;
+    set_next(has_next ? tr.at(t + 1) : 0, has_next);
     const unsigned char* y1s = smem + stage * C::STAGE_BYTES;
     const unsigned char* y2s = y1s + C::TILE0;
     const int y0 = yt * C::BN;
@@ -341,7 +357,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     // memory pipeline takes a 16-byte-per-lane load every few tens of cycles, and a wave that issues
     // its whole share at once sits in that queue instead of feeding the matrix pipe.  A wave with
     // nothing to compute issues them all now.
-    if (kind == kTileEmpty && has_next) gload(yt_next, stage ^ 1);
+    if (kind == kTileEmpty) gload(stage ^ 1);
 
     // Swizzled (direct-to-LDS) tiles: LDS addresses are formed next to each read with one XOR instead of
     // being kept as loop invariants (one register per k-step / feature block otherwise).  For tile row
@@ -431,7 +447,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
         for (int n = 0; n < 16; ++n) {
           const bf16x8 fa = kf[n % PF];
           if (n + PF < 16) kf[n % PF] = kfrag((n + PF) / 8, (n + PF) % 8);
-          if (has_next && n % (16 / C::CPT) == 0) gload_piece(yt_next, n / (16 / C::CPT), stage ^ 1);
+          if (n % (16 / C::CPT) == 0) gload_piece(n / (16 / C::CPT), stage ^ 1);
           __builtin_amdgcn_sched_barrier(0);
           if (n < 8) {
             s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, res[0][n], s0, 0, 0, 0);
@@ -513,7 +529,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
         for (int n = 0; n < 32; ++n) {
           const bf16x8 fa = fr[n % PF];
           if (n + PF < 32) fr[n % PF] = rowfrag(n + PF);
-          if (has_next && n % (32 / C::CPT) == 0) gload_piece(yt_next, n / (32 / C::CPT), stage ^ 1);
+          if (n % (32 / C::CPT) == 0) gload_piece(n / (32 / C::CPT), stage ^ 1);
           __builtin_amdgcn_sched_barrier(0);
           const int sb = n >> 4, ks = (n >> 1) & 7;
           if (n & 1) dp[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, res[1][ks], dp[sb], 0, 0, 0);
@@ -592,9 +608,9 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
               }
             }
             if constexpr (C::KS % C::CPT == 0) {
-              if (sg == 0 && has_next && ks % (C::KS / C::CPT) == 0) gload_piece(yt_next, ks / (C::KS / C::CPT), stage ^ 1);
+              if (sg == 0 && ks % (C::KS / C::CPT) == 0) gload_piece(ks / (C::KS / C::CPT), stage ^ 1);
             } else {
-              if (sg == 0 && has_next && ks == 0) gload(yt_next, stage ^ 1);
+              if (sg == 0 && ks == 0) gload(stage ^ 1);
             }
             __builtin_amdgcn_sched_barrier(0);                           // keep the fetches ahead of the products
 #pragma unroll
@@ -607,7 +623,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
             }
           }
         } else {
-          if (sg == 0 && has_next) gload(yt_next, stage ^ 1);
+          if (sg == 0) gload(stage ^ 1);
 #pragma unroll
           for (int ks = 0; ks < C::KS; ++ks)
 #pragma unroll
@@ -717,7 +733,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
       }
     }
 
-    if (has_next) lstore(stage ^ 1);
+    lstore(stage ^ 1);                                      // also after the last tile: its (empty) loads must have landed before the LDS is given up
     __syncthreads();
   }
 
