@@ -561,8 +561,13 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
       for (int sg = 0; sg < NSB; sg += SBG) {
         // ---- scores of SBG sub-blocks at once: independent accumulators keep the matrix pipe fed
         f32x16 sc1[SBG], sc2[SBG];
-        if (kind == kTileFull && bias_h) {
-          // every pair is visible and the distance is >= 0: seed the accumulators with the bias strip
+        // Mixed tile whose (existing) query rows are all history rows: every visible pair has distance i - j >= 0, which is
+        // what the strip is indexed by, so the scores are seeded like a full tile's and only the mask is applied
+        // per element (no table gathers, whose wait would also wait for the tile being fetched).
+        // (Query-stationary passes only: in the dK/dV pass it measured 2-4 % slower than the gathers.)
+        const bool seeded = MODE != kBwdDKDV && kind == kTilePartial && unit_alpha && bias_h && min(xw0 + 32, L) - 1 < g.n;
+        if ((kind == kTileFull || seeded) && bias_h) {
+          // the distance of every pair that counts is >= 0: seed the accumulators with the bias strip
           const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
 #pragma unroll
           for (int u = 0; u < SBG; ++u)
@@ -652,26 +657,41 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
               }
             }
         } else {
-#pragma unroll
-          for (int u = 0; u < SBG; ++u)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int y = y0 + (sg + u) * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-              int delta;
-              const bool vis = (MODE == kBwdDKDV) ? visible(g, y, x, delta) : visible(g, x, y, delta);
-              float bv = 0.f;
-              if (bias_h) bv = bias_h[vis ? delta : 0];
-              const float sv = fmaf(sc1[u][r], a.alpha, bv);
-              const float sig = sigmoid_l2(sv);
-              const float p = sv * sig;
-              if (MODE == kFwd) {
-                c1[u][r] = vis ? p : 0.f;
-              } else {
-                const float ds = sc2[u][r] * dsilu_l2(p, sig);
-                c1[u][r] = vis ? ds : 0.f;
-                c2[u][r] = vis ? p : 0.f;
-              }
+          // one score of the mixed path: t = score in ln 2 units, vis = pair visible
+          auto mixed = [&](int u, int r, float t, bool vis) {
+            const float sig = sigmoid_l2(t);
+            const float p = t * sig;
+            if (MODE == kFwd) {
+              c1[u][r] = vis ? p : 0.f;
+            } else {
+              const float ds = sc2[u][r] * dsilu_l2(p, sig);
+              c1[u][r] = vis ? ds : 0.f;
+              c2[u][r] = vis ? p : 0.f;
             }
+          };
+          if (seeded) {
+#pragma unroll
+            for (int u = 0; u < SBG; ++u)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int y = y0 + (sg + u) * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+                int delta;
+                const bool vis = (MODE == kBwdDKDV) ? visible(g, y, x, delta) : visible(g, x, y, delta);
+                mixed(u, r, sc1[u][r], vis);
+              }
+          } else {
+#pragma unroll
+            for (int u = 0; u < SBG; ++u)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int y = y0 + (sg + u) * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+                int delta;
+                const bool vis = (MODE == kBwdDKDV) ? visible(g, y, x, delta) : visible(g, x, y, delta);
+                float bv = 0.f;
+                if (bias_h) bv = bias_h[vis ? delta : 0];
+                mixed(u, r, fmaf(sc1[u][r], a.alpha, bv), vis);
+              }
+          }
         }
 
         // ---- second products: out^T[feature][x] += Y^T[feature][y] * coeff[y][x]
