@@ -227,6 +227,47 @@ void oracle_attn_bwd_rows(int B, int H, int d, const int32_t *offsets, const int
     }
 }
 
+/*
+ * Gradient of the relative-bias table.  The bias enters the score additively, s = alpha q.k + table[h, bucket(dist)],
+ * so dL/dtable[h, c] is the sum of ds (as defined above) over the visible pairs of head h whose distance falls in
+ * bucket c.  dtable is [H, nb], fully overwritten.  (The paper has no bias; this follows the benchmark spec of the
+ * layer, like score().)
+ */
+void oracle_attn_bwd_bias(int B, int H, int d, const int32_t *offsets, const int32_t *num_targets, int K1, int K2,
+                          double alpha, double inv_n, const double *table, const int32_t *bounds, int nb,
+                          const double *Q, const double *K, const double *V, const double *dA, double *dtable) {
+    const attn_desc a = make_desc(B, H, d, offsets, num_targets, K1, K2, alpha, inv_n, table, bounds, nb);
+    for (int64_t x = 0; x < (int64_t)H * nb; ++x) dtable[x] = 0.0;
+    if (!table) return;
+    for (int b = 0; b < B; ++b) {
+        const int64_t base = offsets[b];
+        const int L = offsets[b + 1] - offsets[b];
+        const int M = num_targets ? num_targets[b] : 0;
+#pragma omp parallel
+        {
+            double *loc = (double *)calloc((size_t)H * nb, sizeof(double));
+#pragma omp for schedule(dynamic, 4)
+            for (int i = 0; i < L; ++i)
+                for (int h = 0; h < H; ++h) {
+                    const double *da = dA + ((base + i) * H + h) * d;
+                    for (int j = 0; j < L; ++j) {
+                        int delta;
+                        if (!visible(i, j, L, M, K1, K2, &delta)) continue;
+                        const double s = score(&a, Q, K, base + i, base + j, h, delta);
+                        const double sg = sigmoid(s);
+                        const double *v = V + ((base + j) * H + h) * d;
+                        double dw = 0.0;
+                        for (int c = 0; c < d; ++c) dw += da[c] * v[c];
+                        loc[(int64_t)h * nb + bucket_of(bounds, nb, delta)] += dw * sg * (1.0 + s * (1.0 - sg)) * inv_n;
+                    }
+                }
+#pragma omp critical
+            for (int64_t x = 0; x < (int64_t)H * nb; ++x) dtable[x] += loc[x];
+            free(loc);
+        }
+    }
+}
+
 /* visible(i, j) for one sequence as a dense L x L byte matrix, plus the distances (for tests). */
 void oracle_mask(int L, int M, int K1, int K2, uint8_t *mask, int32_t *dist) {
     for (int i = 0; i < L; ++i)

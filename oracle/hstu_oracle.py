@@ -102,6 +102,18 @@ def attn_bwd(q, k, v, dout, offsets, *, num_targets=None, K1=-1, K2=0, alpha=1.0
     return dq, dk, dv
 
 
+def attn_bwd_bias(q, k, v, dout, offsets, *, num_targets=None, K1=-1, K2=0, alpha=1.0, inv_n=1.0, table=None,
+                  bounds=None):
+    """Gradient of the relative-bias table [H, num_buckets] for upstream gradient ``dout`` of ``attn_fwd``."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    T, H, d = q.shape
+    args, keep = _desc(offsets, num_targets, K1, K2, alpha, inv_n, table, bounds, H, d)
+    assert int(keep[0][-1]) == T and table is not None
+    dtable = np.empty((H, np.asarray(bounds).shape[0]), dtype=np.float64)
+    _load().oracle_attn_bwd_bias(*args, _p(q), _p(k), _p(v), _p(dout), _p(dtable))
+    return dtable
+
+
 def mask(L, M=0, K1=-1, K2=0):
     """Dense visibility matrix (bool [L, L]) and bias distances (int32, -1 where masked) of one sequence."""
     m = np.zeros((L, L), dtype=np.uint8)

@@ -75,8 +75,9 @@ def dense_attention_numpy(w: wl.Workload, q=None, k=None, v=None):
     return out
 
 
-def dense_attention_torch(w: wl.Workload, q, k, v):
-    """Same dense formulation in torch fp64 so autograd supplies reference gradients."""
+def dense_attention_torch(w: wl.Workload, q, k, v, table=None):
+    """Same dense formulation in torch fp64 so autograd supplies reference gradients (``table``: the
+    bias table as a torch tensor, when its gradient is wanted too)."""
     outs = []
     for b in range(w.B):
         s0, s1 = int(w.offsets[b]), int(w.offsets[b + 1])
@@ -91,7 +92,8 @@ def dense_attention_torch(w: wl.Workload, q, k, v):
                 S = w.alpha * q[s0:s1, h] @ k[s0:s1, h].T
                 if w.table is not None:
                     bucket = np.searchsorted(w.bounds, dist, side="right") - 1
-                    S = S + torch.from_numpy(w.table[h].astype(np.float64))[torch.from_numpy(bucket)]
+                    row = torch.from_numpy(w.table[h].astype(np.float64)) if table is None else table[h]
+                    S = S + row[torch.from_numpy(bucket)]
                 P = torch.nn.functional.silu(S) / w.N * mask_t
                 heads.append(P @ v[s0:s1, h])
             o = torch.stack(heads, dim=1)
@@ -415,6 +417,50 @@ def test_backward_matches_central_differences():
             argsm = {"q": (minus, k, v), "k": (q, minus, v), "v": (q, k, minus)}[name]
             fd = (loss(*args) - loss(*argsm)) / (2 * h)
             assert abs(fd - grad[idx]) < 1e-7 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
+
+
+@pytest.mark.parametrize("case", range(len(TINY_CASES)))
+def test_bias_table_gradient_matches_autograd_of_dense_formulation(case):
+    w = tiny(300 + case, bias=True, alpha=0.8, N=5.0, **TINY_CASES[case])
+    w.bounds = np.array([0, 1, 2, 4, 7, 12], dtype=np.int32)
+    w.table = np.random.default_rng(16).standard_normal((w.H, 6)).astype(np.float32)
+    q, k, v = (torch.from_numpy(x.astype(np.float64)) for x in (w.q, w.k, w.v))
+    table = torch.from_numpy(w.table.astype(np.float64)).requires_grad_()
+    out = dense_attention_torch(w, q, k, v, table=table)
+    out.backward(torch.from_numpy(w.dout.astype(np.float64)))
+    got = orc.attn_bwd_bias(w.q, w.k, w.v, w.dout, w.offsets, num_targets=w.num_targets, K1=w.K1, K2=w.K2,
+                            alpha=w.alpha, inv_n=1.0 / w.N, table=w.table, bounds=w.bounds)
+    np.testing.assert_allclose(got, table.grad.numpy(), rtol=1e-10, atol=1e-13)
+
+
+def test_bias_table_gradient_matches_central_differences():
+    w = tiny(33, [11, 7], H=2, d=4, bias=True, K1=5, K2=2, num_targets=[3, 0], alpha=1.2, N=4.0)
+    w.bounds = np.array([0, 1, 3, 6], dtype=np.int32)
+    w.table = np.random.default_rng(18).standard_normal((2, 4)).astype(np.float32)
+    g = w.dout.astype(np.float64)
+    kw = dict(num_targets=w.num_targets, K1=5, K2=2, alpha=1.2, inv_n=0.25, bounds=w.bounds)
+    got = orc.attn_bwd_bias(w.q, w.k, w.v, g, w.offsets, table=w.table, **kw)
+    h = 1e-6
+    for hh in range(2):
+        for c in range(4):
+            plus, minus = w.table.astype(np.float64), w.table.astype(np.float64)
+            plus[hh, c] += h
+            minus[hh, c] -= h
+            fd = (float((orc.attn_fwd(w.q, w.k, w.v, w.offsets, table=plus, **kw) * g).sum()) -
+                  float((orc.attn_fwd(w.q, w.k, w.v, w.offsets, table=minus, **kw) * g).sum())) / (2 * h)
+            assert abs(fd - got[hh, c]) < 1e-7 * max(1.0, abs(fd)), (hh, c, fd, got[hh, c])
+
+
+def test_bias_table_gradient_single_pair_closed_form():
+    # one token: the only pair is (0, 0) at distance 0 -> bucket 0;  dL/dtable = (dO . v) silu'(s) / N
+    w = tiny(35, [1], H=1, d=3, bias=True, N=2.0)
+    w.bounds = np.array([0, 5], dtype=np.int32)
+    w.table = np.array([[0.3, -0.7]], dtype=np.float32)
+    got = orc.attn_bwd_bias(w.q, w.k, w.v, w.dout, w.offsets, inv_n=0.5, table=w.table, bounds=w.bounds)
+    s = float(w.q[0, 0].astype(np.float64) @ w.k[0, 0].astype(np.float64)) + float(w.table[0, 0])
+    sg = 1.0 / (1.0 + np.exp(-s))
+    expect = float(w.dout[0, 0].astype(np.float64) @ w.v[0, 0].astype(np.float64)) * sg * (1 + s * (1 - sg)) * 0.5
+    assert abs(got[0, 0] - expect) < 1e-14 and got[0, 1] == 0.0
 
 
 def test_bucket_lookup_edges():
