@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward attention only (profiling aid)")
+    ap.add_argument("--bias-grad", action="store_true",
+                    help="also compute the gradient of the relative-bias table in the attention backward")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (profiling aid: calibrates the HBM byte counters)")
     return ap.parse_args()
@@ -97,7 +99,7 @@ def main():
 
     w = workloads.config(args.workload)
     fl = flops.attention_flops(w)
-    dw = DeviceWorkload(w)
+    dw = DeviceWorkload(w, bias_grad=args.bias_grad)
     do_bwd = w.backward and not args.fwd_only
 
     def step():
@@ -150,7 +152,7 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "pass": "fwd+bwd+epilogue" if do_bwd else "fwd", "B": w.B, "T": w.T, "H": w.H,
+        "config": {"workload": w.name, "pass": ("fwd+bwd+epilogue" if do_bwd else "fwd") + ("+dbias" if args.bias_grad else ""), "B": w.B, "T": w.T, "H": w.H,
                    "d": w.d, "K1": w.K1, "K2": w.K2, "min_len": int(w.lengths.min()), "max_len": int(w.lengths.max()),
                    "unmasked_pairs": fl["pairs"]},
         "frac_of_peak": value / peak,

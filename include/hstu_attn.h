@@ -87,6 +87,9 @@ typedef struct hstu_attn_params {
   const float* rab_table;   /* DEVICE fp32[H, num_buckets] or NULL = no bias */
   const int32_t* rab_bounds;/* DEVICE int32[num_buckets], strictly increasing, [0] = 0 (NULL iff rab_table NULL) */
   int32_t num_buckets;      /* in [1, 4096] when rab_table is given */
+  float* d_rab_table;       /* hstu_attn_bwd only, optional: DEVICE fp32[H, num_buckets] receives the gradient of
+                               rab_table (sum of dS over the visible pairs of each bucket), overwritten; NULL = not
+                               wanted; ignored by hstu_attn_fwd; requires rab_table */
 } hstu_attn_params;
 
 /* Bytes of device scratch (256-byte aligned) that hstu_attn_fwd (for_backward = 0)
@@ -105,8 +108,10 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
 
 /* Backward of Eq. 3 (attention_backward(dattn, q, k, v) -> dq, dk, dv): the scores are
  * recomputed from q, k; nothing saved by the forward is needed.  dout uses row_stride_o,
- * dq/dk/dv use the strides of q/k/v.  The bias table receives no gradient.  Deterministic:
- * no atomics; partial sums of cut key blocks are added in a fixed order. */
+ * dq/dk/dv use the strides of q/k/v.  dq, dk, dv are deterministic: no atomics; partial sums
+ * of cut key blocks are added in a fixed order.  With p->d_rab_table set the dQ pass also sums
+ * dS per distance with fp32 atomics (run-to-run differences at rounding level) and a small
+ * kernel folds the distances into buckets. */
 int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, const void* dout,
                   void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
 
@@ -139,7 +144,8 @@ int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, i
  * launch made by the entry points above is bracketed by HIP events on its stream (up to 16 launches
  * between two reads).  hstu_profile_read waits for those events and returns the number of entries
  * written: names[i] (static strings: "attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "gated_norm_fwd",
- * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_fwd", "schedule_bwd" [both backward lists, one launch], "bias_expand") and
+ * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_fwd", "schedule_bwd" [both backward lists, one launch], "bias_expand", "dbias_zero", "dbias_reduce";
+ * "attn_bwd_dkdv" includes the kernel that combines the partial sums of cut key blocks) and
  * ms[i] = elapsed milliseconds.  HOST arrays.  Not thread-safe; enable(1) creates the events once. */
 int hstu_profile_enable(int on);
 int hstu_profile_read(int max_entries, const char** names, float* ms);

@@ -17,7 +17,7 @@ inline int64_t max_items_for(const hstu_attn_params* p, int block_rows) {
 }
 
 struct Layout {           // byte offsets inside a workspace
-  size_t header[2], items[2], seq_base[2], bias, splits, partial, total;
+  size_t header[2], items[2], seq_base[2], bias, splits, partial, dbias, total;
   int max_items[2];
   int slot_cap;           // partial-sum slots of the dK/dV pass (key blocks cut along the query axis)
 };
@@ -51,6 +51,8 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
     l.splits = off; off += align_up((size_t)(l.slot_cap / 2 + 1) * sizeof(SplitItem));
     l.partial = off;
     off += align_up((size_t)l.slot_cap * 2 * dkv_block_rows(p->dtype, p->head_dim) * p->head_dim * sizeof(float));
+    l.dbias = off;                                     // per-distance sums of dS for the bias-table gradient
+    off += align_up((size_t)p->num_heads * ((size_t)p->max_seqlen + 1) * sizeof(float));
   }
   l.total = off;
   return l;
@@ -76,6 +78,7 @@ int validate(const hstu_attn_params* p) {
   if (p->global_prefix < 0) return HSTU_ERR_SHAPE;
   if ((p->rab_table == nullptr) != (p->rab_bounds == nullptr)) return HSTU_ERR_NULL;
   if (p->rab_table && (p->num_buckets < 1 || p->num_buckets > 4096)) return HSTU_ERR_SHAPE;
+  if (p->d_rab_table && !p->rab_table) return HSTU_ERR_NULL;
   if ((int64_t)p->total_tokens * p->num_heads / 32 + (int64_t)p->batch * p->num_heads > 0x7FFFFF00) return HSTU_ERR_SHAPE;
   if (p->seq_offsets_host) {
     const int32_t* o = p->seq_offsets_host;
@@ -249,16 +252,29 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
     if (launch_schedule_pair(a, rows, cols, hd, it, sb, (SplitItem*)(ws + l.splits), l.slot_cap, stream) != hipSuccess)
       return HSTU_ERR_LAUNCH;
   }
+  if (p->d_rab_table) {
+    ProfScope ps("dbias_zero", stream);
+    a.dbias_dist = (float*)(ws + l.dbias);
+    if (launch_fill_zero(a.dbias_dist, (size_t)p->num_heads * a.bias_stride, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  }
   for (int s = 0; s < 2; ++s) {                          // s = 0: dQ pass (query blocks), s = 1: dK/dV pass (key blocks)
     a.max_items = l.max_items[s];
     a.header = (const SchedHeader*)(ws + l.header[s]);
     a.items = (const WorkItem*)(ws + l.items[s]);
     a.partial = (float*)(ws + l.partial);
     a.splits = (const SplitItem*)(ws + l.splits);
-    ProfScope ps(s == 0 ? "attn_bwd_dq" : "attn_bwd_dkdv", stream);
-    const hipError_t e = s == 0 ? launch_attn_bwd_dq(a, p->dtype, stream) : launch_attn_bwd_dkdv(a, p->dtype, stream);
-    if (e != hipSuccess) return HSTU_ERR_LAUNCH;
-    if (s == 1 && launch_dkdv_combine(a, p->dtype, l.slot_cap / 2, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    {
+      ProfScope ps(s == 0 ? "attn_bwd_dq" : "attn_bwd_dkdv", stream);     // the dK/dV figure includes its combine kernel
+      const hipError_t e = s == 0 ? launch_attn_bwd_dq(a, p->dtype, stream) : launch_attn_bwd_dkdv(a, p->dtype, stream);
+      if (e != hipSuccess) return HSTU_ERR_LAUNCH;
+      if (s == 1 && launch_dkdv_combine(a, p->dtype, l.slot_cap / 2, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    }
+    if (s == 0 && p->d_rab_table) {
+      ProfScope ps2("dbias_reduce", stream);
+      if (launch_dbias_reduce(a.dbias_dist, p->rab_bounds, p->num_buckets, p->num_heads, a.bias_stride, p->inv_n,
+                              p->d_rab_table, stream) != hipSuccess)
+        return HSTU_ERR_LAUNCH;
+    }
   }
   return HSTU_OK;
 }

@@ -82,6 +82,11 @@ struct Cfg {
   static constexpr int STAT_BASE = 2 * STAGE_BYTES + 2 * STRIP_BYTES;
   static constexpr int STAT_BYTES = kStatLds ? BX * ROW_BYTES : 0;      // stationary operand 1, same swizzle as the tiles
   static constexpr int SMEM_BYTES = STAT_BASE + STAT_BYTES;             // 2 stages x (2 tensors + strip) [+ stationary rows]
+  // bias-gradient variant of the dQ pass: two (double-buffered) strips of per-distance sums behind everything else
+  static constexpr int DACC_LEN = (BX + BN - 1 + 63) / 64 * 64;
+  static constexpr int DACC_BASE = SMEM_BYTES;
+  static constexpr int DACC_COPIES = 2 * NWAVES;                 // one strip per (wave, half-wave): every address has one owner lane, plain read-add-write
+  static constexpr int DACC_BYTES = 2 * DACC_COPIES * DACC_LEN * 4;
 };
 
 template <typename E> struct ResidentFrag;
@@ -107,8 +112,11 @@ __device__ __forceinline__ float sigmoid_l2(float t) {           // sigmoid(t * 
 // dS / dP = sigmoid (1 + s (1 - sigmoid)) = sigmoid + (t sigmoid) * ln2 (1 - sigmoid)
 __device__ __forceinline__ float dsilu_l2(float tp, float sig) { return fmaf(tp, fmaf(-kLn2, sig, kLn2), sig); }
 
-template <typename E, int D, int MODE, int NWAVES>
+// DBIAS (dQ pass only): also sum dS along the diagonals of every tile (pairs of equal distance i - j) into
+// a.dbias_dist[h, distance]; dbias_reduce_kernel folds distances into buckets afterwards.
+template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false>
 __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 2 : 1)) void attn_kernel(const AttnArgs a) {
+  static_assert(!DBIAS || MODE == kBwdDQ, "the bias gradient rides with the dQ pass");
   using C = Cfg<E, D, MODE, NWAVES>;
   using RFrag = typename ResidentFrag<E>::type;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -330,6 +338,39 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
       dma16(tile_rsrc(R2, rowb, x0 + 4 * rg), voff, dst);
     }
   }
+  // ---- bias gradient (DBIAS): dacc[p][s] collects dS of tile parity p along strip index
+  // s = (y - tile start) + (BX - 1 - (x - x0)), i.e. distance x - y = x0 + BX - 1 - tile start - s
+  float* dacc = (float*)(smem + C::DACC_BASE);
+  const int dacc_lane = (wave * 2 + hf) * C::DACC_LEN + C::BX - 1 - (wave * 32 + l32) + 4 * hf;   // + 32 * sub-block + 8 * (r / 4) + r % 4
+  auto dacc_flush = [&](int parity, int yt_of) {                         // every wave has passed the barrier after that tile
+    if constexpr (DBIAS) {
+      if (a.dbias_dist && tid < C::BX + C::BN - 1) {
+        float vsum = 0.f;
+#pragma unroll
+        for (int c = 0; c < C::DACC_COPIES; ++c) {
+          vsum += dacc[(parity * C::DACC_COPIES + c) * C::DACC_LEN + tid];
+          dacc[(parity * C::DACC_COPIES + c) * C::DACC_LEN + tid] = 0.f;
+        }
+        const int dist = x0 + C::BX - 1 - yt_of * C::BN - tid;
+        if (vsum != 0.f && dist >= 0 && dist < a.bias_stride) atomicAdd(a.dbias_dist + (int64_t)h * a.bias_stride + dist, vsum);
+      }
+    }
+  };
+  // adds the 16 scores-gradients this lane holds for one 32-row sub-block of the tile in `stage` (LDS float
+  // atomics run one lane per cycle on this part; the private strips make them unnecessary)
+  auto dacc_add = [&](int stage, int sub, const float* vals) {
+    // Lanes of one instruction own distinct addresses of their (wave, half) strip, but the same address comes up
+    // again in other registers of other lanes (that is the diagonal sum): one register at a time.
+    float* base = dacc + stage * C::DACC_COPIES * C::DACC_LEN + dacc_lane + sub * 32;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      volatile float* p = base + 8 * (r >> 2) + (r & 3);
+      *p = *p + vals[r];
+    }
+  };
+  if constexpr (DBIAS) {
+    for (int i = tid; i < 2 * C::DACC_COPIES * C::DACC_LEN; i += C::NT) dacc[i] = 0.f;
+  }
   set_next(t_begin < ntiles ? tr.at(t_begin) : 0, t_begin < ntiles);
   gload(0);
   lstore(0);
@@ -342,6 +383,9 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     const int stage = (t - t_begin) & 1;
     const bool has_next = t + 1 < ntiles;
     set_next(has_next ? tr.at(t + 1) : 0, has_next);
+    if constexpr (DBIAS) {
+      if (t > t_begin) dacc_flush(stage ^ 1, tr.at(t - 1));
+    }
     const unsigned char* y1s = smem + stage * C::STAGE_BYTES;
     const unsigned char* y2s = y1s + C::TILE0;
     const int y0 = yt * C::BN;
@@ -498,6 +542,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
         };
         f32x16 sv[2], dp[2];
         uint32_t pds[2][8], pp[2][8];
+        float dsf[DBIAS ? 2 : 1][16];                                      // dS in fp32 for the bias gradient
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
           if (bias_h) {
@@ -518,8 +563,10 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
           const float s0v = sv[sb][2 * m], s1v = sv[sb][2 * m + 1];
           const float g0 = sigmoid_l2(s0v), g1 = sigmoid_l2(s1v);
           const float p0v = s0v * g0, p1v = s1v * g1;
-          pds[sb][m] = pack_bf16x2(dp[sb][2 * m] * dsilu_l2(p0v, g0), dp[sb][2 * m + 1] * dsilu_l2(p1v, g1));
+          const float ds0 = dp[sb][2 * m] * dsilu_l2(p0v, g0), ds1 = dp[sb][2 * m + 1] * dsilu_l2(p1v, g1);
+          pds[sb][m] = pack_bf16x2(ds0, ds1);
           if constexpr (MODE == kBwdDKDV) pp[sb][m] = pack_bf16x2(p0v, p1v);
+          if constexpr (DBIAS) { dsf[sb][2 * m] = ds0; dsf[sb][2 * m + 1] = ds1; }
         };
         constexpr int PF = (MODE == kBwdDQ) ? 2 : 4;                      // the dQ pass runs two waves per SIMD: 256 registers
         bf16x8 fr[PF];
@@ -537,6 +584,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
           if (n >= 16 && (n & 1)) pointwise(0, (n - 16) >> 1);
           __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (DBIAS) dacc_add(stage, 0, dsf[0]);                  // fully visible tile: history rows, distance x - y
         constexpr int NO = 16 * C::NOUT;                                  // output products of the tile
 #pragma unroll
         for (int i = 0; i < PF; ++i) fr[i] = trfrag(i);
@@ -553,6 +601,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
           if (sb == 0 && o == C::NOUT - 1) pointwise(1, step);
           __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (DBIAS) dacc_add(stage, 1, dsf[1]);
         done = true;
       }
     }
@@ -694,6 +743,25 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
           }
         }
 
+        if constexpr (DBIAS) {
+          // dS per distance: history rows add along the tile's diagonals in LDS; candidate rows (their distance
+          // is n - j, not i - j) are few and add to the global table directly
+#pragma unroll
+          for (int u = 0; u < SBG; ++u) {
+            float hv[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              hv[r] = x < g.n ? c1[u][r] : 0.f;
+              if (x >= g.n && c1[u][r] != 0.f) {
+                int delta;
+                if (visible(g, x, y0 + (sg + u) * 32 + 8 * (r >> 2) + 4 * hf + (r & 3), delta))
+                  atomicAdd(a.dbias_dist + (int64_t)h * a.bias_stride + delta, c1[u][r]);
+              }
+            }
+            dacc_add(stage, sg + u, hv);
+          }
+        }
+
         // ---- second products: out^T[feature][x] += Y^T[feature][y] * coeff[y][x]
         if constexpr (C::kBf16) {
           // transpose load: within a group of 16 lanes, lane 4r+c supplies the address of 4 features
@@ -757,6 +825,9 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
     __syncthreads();
   }
 
+  if constexpr (DBIAS) {
+    if (ntiles > t_begin) dacc_flush((ntiles - 1 - t_begin) & 1, tr.at(ntiles - 1));
+  }
   // ---- epilogue: scale once, convert, store.  Lane x holds features ob*32 + 8*(r/4) + 4*hf + r%4.
   if constexpr (MODE == kBwdDKDV) {
     if (item.slot >= 0) {
@@ -827,36 +898,37 @@ __global__ __launch_bounds__(256) void dkdv_combine_kernel(const AttnArgs a, int
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename E, int D, int MODE, int NWAVES>
+template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false>
 static hipError_t launch_one(const AttnArgs& a, hipStream_t stream) {
   using C = Cfg<E, D, MODE, NWAVES>;
-  auto kern = attn_kernel<E, D, MODE, NWAVES>;
+  auto kern = attn_kernel<E, D, MODE, NWAVES, DBIAS>;
+  constexpr int smem_bytes = C::SMEM_BYTES + (DBIAS ? C::DACC_BYTES : 0);
   static bool attr_set = false;                                          // per instantiation
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int per = kNumXcd * kXcdGroup;
   const int grid = (a.max_items + per - 1) / per * per;
   if (grid == 0) return hipSuccess;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::SMEM_BYTES, stream, a);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), smem_bytes, stream, a);
   return hipGetLastError();
 }
 
-template <int MODE, int NW_BF16, int NW_FP32>
+template <int MODE, int NW_BF16, int NW_FP32, bool DBIAS = false>
 static hipError_t dispatch(const AttnArgs& a, int dtype, hipStream_t stream) {
   if (dtype == 0) {
     switch (a.D) {
-      case 32: return launch_one<__bf16, 32, MODE, NW_BF16>(a, stream);
-      case 64: return launch_one<__bf16, 64, MODE, NW_BF16>(a, stream);
-      case 128: return launch_one<__bf16, 128, MODE, NW_BF16>(a, stream);
+      case 32: return launch_one<__bf16, 32, MODE, NW_BF16, DBIAS>(a, stream);
+      case 64: return launch_one<__bf16, 64, MODE, NW_BF16, DBIAS>(a, stream);
+      case 128: return launch_one<__bf16, 128, MODE, NW_BF16, DBIAS>(a, stream);
     }
   } else {
     switch (a.D) {
-      case 32: return launch_one<float, 32, MODE, NW_FP32>(a, stream);
-      case 64: return launch_one<float, 64, MODE, NW_FP32>(a, stream);
-      case 128: return launch_one<float, 128, MODE, NW_FP32>(a, stream);
+      case 32: return launch_one<float, 32, MODE, NW_FP32, DBIAS>(a, stream);
+      case 64: return launch_one<float, 64, MODE, NW_FP32, DBIAS>(a, stream);
+      case 128: return launch_one<float, 128, MODE, NW_FP32, DBIAS>(a, stream);
     }
   }
   return hipErrorInvalidValue;
@@ -876,7 +948,43 @@ hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream) {
   return dispatch<kFwd, kFwdWavesBf16, kFwdWavesFp32>(a, dtype, stream);
 }
 hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream) {
+  if (a.dbias_dist) return dispatch<kBwdDQ, kDqWavesBf16, kDqWavesFp32, true>(a, dtype, stream);
   return dispatch<kBwdDQ, kDqWavesBf16, kDqWavesFp32>(a, dtype, stream);
+}
+
+// dtable[h, c] = scale * sum of dist[h, x] over the distances x of bucket c (bounds[c] <= x < bounds[c+1], x < len).
+// One workgroup per (bucket, head); fixed-order tree reduction.
+__global__ __launch_bounds__(256) void dbias_reduce_kernel(const float* __restrict__ dist, const int32_t* __restrict__ bounds,
+                                                           int nb, int len, float scale, float* __restrict__ dtable) {
+  __shared__ float red[256];
+  const int c = blockIdx.x, h = blockIdx.y;
+  const int lo = min(bounds[c], len), hi = c + 1 < nb ? min(bounds[c + 1], len) : len;
+  float acc = 0.f;
+  for (int x = lo + threadIdx.x; x < hi; x += 256) acc += dist[(size_t)h * len + x];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) dtable[(size_t)h * nb + c] = red[0] * scale;
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)min((n + 255) / 256, (size_t)1024)), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_dbias_reduce(const float* dist, const int32_t* bounds, int num_buckets, int H, int len, float scale,
+                               float* dtable, hipStream_t stream) {
+  hipLaunchKernelGGL(dbias_reduce_kernel, dim3(num_buckets, H), dim3(256), 0, stream, dist, bounds, num_buckets, len, scale,
+                     dtable);
+  return hipGetLastError();
 }
 hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream) {
   return dispatch<kBwdDKDV, kDkvWavesBf16, kDkvWavesFp32>(a, dtype, stream);

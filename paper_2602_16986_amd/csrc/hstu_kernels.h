@@ -44,6 +44,7 @@ struct AttnArgs {
   int32_t max_items;
   float* partial;                   // dK/dV pass: fp32 partial sums [slot][dK, dV][block row][D] of cut key blocks
   const SplitItem* splits;
+  float* dbias_dist;                // dQ pass, optional: sum of dS per head and distance [H, bias_stride] (zeroed by the caller)
 };
 
 // schedule.hip
@@ -68,6 +69,10 @@ int dkv_tile_rows(int dtype, int D);      // ... in the dK/dV pass
 hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream);
+// bias-table gradient: clear the per-distance sums, fold them into buckets (times `scale`) after the dQ pass
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream);
+hipError_t launch_dbias_reduce(const float* dist, const int32_t* bounds, int num_buckets, int H, int len, float scale,
+                               float* dtable, hipStream_t stream);
 // adds the partial sums of every cut key block in piece order, scales, converts and writes dK, dV
 hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream);
 

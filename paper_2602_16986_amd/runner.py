@@ -19,7 +19,7 @@ def _dev(x: np.ndarray, dtype: str, device) -> torch.Tensor:
 class DeviceWorkload:
     """Device-resident copy of a Workload plus output and scratch buffers."""
 
-    def __init__(self, w: Workload, device="cuda:0", fused_qkvu: bool = False):
+    def __init__(self, w: Workload, device="cuda:0", fused_qkvu: bool = False, bias_grad: bool = False):
         self.w = w
         self.device = torch.device(device)
         dt = w.dtype
@@ -54,10 +54,12 @@ class DeviceWorkload:
         self.dgamma = torch.empty(w.H * w.d, dtype=torch.float32, device=self.device)
         self.mean = torch.empty(w.T, dtype=torch.float32, device=self.device)
         self.rstd = torch.empty(w.T, dtype=torch.float32, device=self.device)
+        # optional gradient of the bias table, written by the attention backward
+        self.dtable = torch.empty_like(self.table) if (bias_grad and self.table is not None) else None
         self.problem = hb.AttnProblem(self.q, self.k, self.v, self.out, self.offsets, max_seqlen=w.max_seqlen,
                                       seq_offsets_host=w.offsets, num_targets=self.num_targets,
                                       local_window=w.K1, global_prefix=w.K2, alpha=w.alpha, inv_n=1.0 / w.N,
-                                      rab_table=self.table, rab_bounds=self.bounds)
+                                      rab_table=self.table, rab_bounds=self.bounds, d_rab_table=self.dtable)
         self.ws_fwd = hb.new_workspace(hb.hstu_attn_workspace_bytes(self.problem, False), self.device)
         self.ws_bwd = hb.new_workspace(hb.hstu_attn_workspace_bytes(self.problem, True), self.device)
         self.ws_norm = hb.new_workspace(hb.hstu_gated_norm_bwd_workspace_bytes(w.T, w.H * w.d), self.device)

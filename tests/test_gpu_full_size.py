@@ -110,3 +110,23 @@ def test_causality_and_empty_sequences_on_gpu():
     wd = wl.build("dense", [700, 0, 300], 2, 128, "bf16", seed=3)
     ww = wl.build("wide", [700, 0, 300], 2, 128, "bf16", seed=3, K1=700, K2=0)
     assert torch.equal(DeviceWorkload(wd).attn_fwd(), DeviceWorkload(ww).attn_fwd())
+
+
+def test_bias_table_gradient_at_c2_scale():
+    """Gradient of the bias table on the 512-2048 configuration (42 k tokens, 1.3e8 pairs per head set): every
+    bucket against the oracle."""
+    import torch
+    from oracle import hstu_oracle as orc
+    from paper_2602_16986_amd import workloads as wl
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.config("C2")
+    dw = DeviceWorkload(w, bias_grad=True)
+    dw.attn_bwd()
+    torch.cuda.synchronize()
+    got = dw.dtable.float().cpu().numpy().astype(np.float64)
+    ref = orc.attn_bwd_bias(w.q, w.k, w.v, w.dout, w.offsets, K1=w.K1, K2=w.K2, alpha=w.alpha, inv_n=1.0 / w.N,
+                            table=w.table, bounds=w.bounds)
+    err = np.abs(got - ref).max()
+    scale = np.abs(ref).max()
+    print(f"  dtable C2: max_abs_err={err:.3e} max|ref|={scale:.3e}", flush=True)
+    assert err <= 2e-2 * max(1.0, scale) and err / scale <= 2e-2

@@ -195,3 +195,38 @@ def test_backward_cut_key_blocks_d64_and_fp32(hb):
     run_case(w)
     w = wl.build("cut-fp32", rng.integers(600, 900, size=3), 2, 32, "fp32", rng=rng, K1=40, K2=100, backward=True)
     run_case(w)
+
+
+def bias_gradient_case(w):
+    """d table of hstu_attn_bwd (p->d_rab_table) against the oracle; dq, dk, dv must not change with it."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    tol = TOL[w.dtype]
+    dw = DeviceWorkload(w, bias_grad=True)
+    dw.dtable.fill_(float("nan"))
+    dq, dk, dv = (to_np(t) for t in dw.attn_bwd())
+    torch.cuda.synchronize()
+    ref = orc.attn_bwd_bias(w.q, w.k, w.v, w.dout, w.offsets, **oracle_args(w))
+    check("dtable", to_np(dw.dtable), ref, tol)
+    plain = DeviceWorkload(w)
+    pq, pk, pv = (to_np(t) for t in plain.attn_bwd())
+    torch.cuda.synchronize()
+    assert np.array_equal(dq, pq) and np.array_equal(dk, pk) and np.array_equal(dv, pv)
+
+
+@pytest.mark.parametrize("name", wl.SMALL_CASES)
+def test_bias_table_gradient_small_cases(hb, name):
+    w = wl.small(name)
+    if w.table is None:
+        pytest.skip("case without a bias table")
+    bias_gradient_case(w)
+
+
+def test_bias_table_gradient_general_alpha_and_targets(hb):
+    rng = np.random.default_rng(91)
+    L = rng.integers(100, 700, size=5)
+    w = wl.build("dbias-alpha", L, 2, 128, "bf16", rng=rng, K1=150, K2=40, alpha=0.5, backward=True,
+                 num_targets=np.array([17, 0, 33, 5, 64], dtype=np.int32))
+    bias_gradient_case(w)
+    w = wl.build("dbias-fp32", rng.integers(50, 300, size=3), 2, 64, "fp32", rng=rng, backward=True,
+                 num_targets=np.array([3, 0, 9], dtype=np.int32))
+    bias_gradient_case(w)
