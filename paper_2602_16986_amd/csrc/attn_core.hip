@@ -85,7 +85,7 @@ struct Cfg {
   // bias-gradient variant of the dQ pass: two (double-buffered) strips of per-distance sums behind everything else
   static constexpr int DACC_LEN = (BX + BN - 1 + 63) / 64 * 64;
   static constexpr int DACC_BASE = SMEM_BYTES;
-  static constexpr int DACC_COPIES = 2 * NWAVES;                 // one strip per (wave, half-wave): every address has one owner lane, plain read-add-write
+  static constexpr int DACC_COPIES = NWAVES;                     // one strip per wave: plain read-add-write, no LDS atomics
   static constexpr int DACC_BYTES = 2 * DACC_COPIES * DACC_LEN * 4;
 };
 
@@ -111,6 +111,25 @@ __device__ __forceinline__ float sigmoid_l2(float t) {           // sigmoid(t * 
 }
 // dS / dP = sigmoid (1 + s (1 - sigmoid)) = sigmoid + (t sigmoid) * ln2 (1 - sigmoid)
 __device__ __forceinline__ float dsilu_l2(float tp, float sig) { return fmaf(tp, fmaf(-kLn2, sig, kLn2), sig); }
+
+// One register of the diagonal sum of a 32 x 32 score-gradient block (lane = query 16*a + b of the block, register R
+// = key yo = 8*(R/4) + R%4 (+4 for the upper half-wave)).  Rotating register R by rho = yo % 16 lanes inside its
+// 16-lane row puts every value next to the others of its diagonal: at lane b' it belongs to strip offset
+// 16*j - b' with j = yo/16 + (1 if it came around the row end), so three running sums per lane collect all 16.
+template <int R>
+__device__ __forceinline__ void diag_step(const float* vals, int bq, float& x0, float& x1, float& x2) {
+  constexpr int q = R >> 2, rho = 8 * (q & 1) + (R & 3);
+  float rv = vals[R];
+  if constexpr (rho != 0)                                                // row_ror:(16 - rho): lane b' reads lane (b' + rho) % 16
+    rv = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, rv), 0x120 + (16 - rho), 0xF, 0xF, false));
+  const bool wrapped = bq >= 16 - rho;
+  const float lo = wrapped ? 0.f : rv, hi = wrapped ? rv : 0.f;
+  if constexpr ((q >> 1) == 0) { x0 += lo; x1 += hi; } else { x1 += lo; x2 += hi; }
+}
+template <int... R>
+__device__ __forceinline__ void diag_all(std::integer_sequence<int, R...>, const float* vals, int bq, float& x0, float& x1, float& x2) {
+  (diag_step<R>(vals, bq, x0, x1, x2), ...);
+}
 
 // DBIAS (dQ pass only): also sum dS along the diagonals of every tile (pairs of equal distance i - j) into
 // a.dbias_dist[h, distance]; dbias_reduce_kernel folds distances into buckets afterwards.
@@ -341,7 +360,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
   // ---- bias gradient (DBIAS): dacc[p][s] collects dS of tile parity p along strip index
   // s = (y - tile start) + (BX - 1 - (x - x0)), i.e. distance x - y = x0 + BX - 1 - tile start - s
   float* dacc = (float*)(smem + C::DACC_BASE);
-  const int dacc_lane = (wave * 2 + hf) * C::DACC_LEN + C::BX - 1 - (wave * 32 + l32) + 4 * hf;   // + 32 * sub-block + 8 * (r / 4) + r % 4
+  const int dacc_lane = wave * C::DACC_LEN + C::BX - 1 - wave * 32 + 4 * hf - (lane & 15) - 16 * ((lane >> 4) & 1);   // + 32 * sub-block + 16 * class
   auto dacc_flush = [&](int parity, int yt_of) {                         // every wave has passed the barrier after that tile
     if constexpr (DBIAS) {
       if (a.dbias_dist && tid < C::BX + C::BN - 1) {
@@ -359,14 +378,22 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kTwoPerCu ? 
   // adds the 16 scores-gradients this lane holds for one 32-row sub-block of the tile in `stage` (LDS float
   // atomics run one lane per cycle on this part; the private strips make them unnecessary)
   auto dacc_add = [&](int stage, int sub, const float* vals) {
-    // Lanes of one instruction own distinct addresses of their (wave, half) strip, but the same address comes up
-    // again in other registers of other lanes (that is the diagonal sum): one register at a time.
+    float x0 = 0.f, x1 = 0.f, x2 = 0.f;
+    diag_all(std::make_integer_sequence<int, 16>{}, vals, lane & 15, x0, x1, x2);
+    // Strip index of class j at this lane: dacc_lane + 32 * sub + 16 * j.  Two lanes of a wave meet at one address
+    // (different half-waves, different classes), so the half-waves and the classes take turns.
     float* base = dacc + stage * C::DACC_COPIES * C::DACC_LEN + dacc_lane + sub * 32;
+    const int room = C::DACC_LEN - (dacc_lane - wave * C::DACC_LEN + sub * 32);   // entries from base to the end of the strip
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      volatile float* p = base + 8 * (r >> 2) + (r & 3);
-      *p = *p + vals[r];
-    }
+    for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const float xv = j == 0 ? x0 : (j == 1 ? x1 : x2);
+        if (hf == hs && 16 * j < room) {                                 // beyond the strip only zeros would land
+          volatile float* p = base + 16 * j;
+          *p = *p + xv;
+        }
+      }
   };
   if constexpr (DBIAS) {
     for (int i = tid; i < 2 * C::DACC_COPIES * C::DACC_LEN; i += C::NT) dacc[i] = 0.f;
