@@ -24,8 +24,8 @@ PEAK_HBM_GBS = 8000.0
 # bytes behind the L2 per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/attention_c3_dense_counters.md (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration
 # against a plain 1 GiB copy); only known for the workload that was profiled
-MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 4.567e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 4.722e9 + 0.090e9,
-                          ("C3-dense", "attn_bwd_dkdv"): 4.616e9 + 0.180e9}
+MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 4.696e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 5.041e9 + 0.090e9,
+                          ("C3-dense", "attn_bwd_dkdv"): 4.470e9 + 0.180e9}
 
 
 def parse():
