@@ -205,7 +205,7 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
   a.items = (const WorkItem*)(ws + l.items[0]);
   {
     ProfScope ps("schedule_fwd", stream);
-    if (launch_schedule(a, fwd_block_rows(p->dtype, p->head_dim), stream_tile_rows(p->dtype, p->head_dim), false,
+    if (launch_schedule(a, fwd_block_rows(p->dtype, p->head_dim), fwd_tile_rows(p->dtype, p->head_dim), false,
                         (SchedHeader*)(ws + l.header[0]), (WorkItem*)(ws + l.items[0]), (int32_t*)(ws + l.seq_base[0]),
                         stream) != hipSuccess)
       return HSTU_ERR_LAUNCH;

@@ -64,7 +64,8 @@ hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num
 int fwd_block_rows(int dtype, int D);     // query rows per workgroup, forward
 int dq_block_rows(int dtype, int D);      // query rows per workgroup, dQ pass
 int dkv_block_rows(int dtype, int D);     // key rows per workgroup, dK/dV pass
-int stream_tile_rows(int dtype, int D);   // rows of one streamed LDS tile (forward, dQ pass)
+int stream_tile_rows(int dtype, int D);   // rows of one streamed LDS tile (dQ pass)
+int fwd_tile_rows(int dtype, int D);      // ... in the forward
 int dkv_tile_rows(int dtype, int D);      // ... in the dK/dV pass
 hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream);
