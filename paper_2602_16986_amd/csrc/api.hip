@@ -225,7 +225,12 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
                   void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream_) {
   const int st = validate(p);
   if (st != HSTU_OK) return st;
-  if (p->total_tokens == 0 || p->batch == 0) return HSTU_OK;
+  if (p->total_tokens == 0 || p->batch == 0) {           // no pairs: the only output that still exists is a zero table gradient
+    if (p->d_rab_table &&
+        launch_fill_zero(p->d_rab_table, (size_t)p->num_heads * p->num_buckets, (hipStream_t)stream_) != hipSuccess)
+      return HSTU_ERR_LAUNCH;
+    return HSTU_OK;
+  }
   if (!q || !k || !v || !dout || !dq || !dk || !dv) return HSTU_ERR_NULL;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(dout) || misaligned(dq) || misaligned(dk) ||
       misaligned(dv))

@@ -856,11 +856,13 @@ static hipError_t launch_one(const AttnArgs& a, hipStream_t stream) {
   using C = Cfg<E, D, MODE, NWAVES>;
   auto kern = attn_kernel<E, D, MODE, NWAVES, DBIAS>;
   constexpr int smem_bytes = C::SMEM_BYTES + (DBIAS ? C::DACC_BYTES : 0);
-  static bool attr_set = false;                                          // per instantiation
-  if (!attr_set) {
+  static bool attr_set[64] = {};                                         // per instantiation and device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+  if (dev < 0 || dev >= 64 || !attr_set[dev]) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    if (dev >= 0 && dev < 64) attr_set[dev] = true;
   }
   const int per = kNumXcd * kXcdGroup;
   const int grid = (a.max_items + per - 1) / per * per;
