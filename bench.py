@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--fwd-only", action="store_true", help="time the forward attention only (profiling aid)")
     ap.add_argument("--bias-grad", action="store_true",
                     help="also compute the gradient of the relative-bias table in the attention backward")
+    ap.add_argument("--op", default="attention", choices=["attention", "truncate"],
+                    help="attention: the hot path (default).  truncate: the row selection of attention truncation "
+                         "(Section 4.3) on the AT-3072-512 batch, forward + backward, in GB/s against the HBM roofline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (profiling aid: calibrates the HBM byte counters)")
     return ap.parse_args()
@@ -86,12 +89,72 @@ def cpu_baseline(w, fl, target_seconds):
                       f"{' + backward (dQ, dK, dV rows)' if w.backward else ''}, fp64, {dt:.1f} s"}
 
 
+def bench_truncate(args):
+    """Row selection of attention truncation: offsets + gather (forward), scatter with zero fill (backward).
+    Algorithmic bytes: forward reads and writes the kept rows (2 x T' x row bytes); backward reads the kept
+    rows' gradient and writes every row of the untruncated gradient ((T' + T) x row bytes)."""
+    import torch
+    from paper_2602_16986_amd import binding as hb
+    from paper_2602_16986_amd import workloads
+    c = workloads.truncation_case("AT-3072-512")
+    dev = torch.device("cuda:0")
+    off = torch.from_numpy(c.offsets).to(dev)
+    x = torch.from_numpy(c.x.view(np.int16)).to(dev)
+    new_off = torch.empty(len(c.lengths) + 1, dtype=torch.int32, device=dev)
+    cap = min(x.shape[0], len(c.lengths) * c.keep)
+    y = torch.empty(cap, c.width, dtype=x.dtype, device=dev)
+    dx = torch.empty_like(x)
+
+    def step():
+        hb.hstu_truncate_offsets(off, c.keep, None, new_off)
+        hb.hstu_truncate_fwd(off, new_off, x, y)
+        hb.hstu_truncate_bwd(off, new_off, y, dx)
+
+    for _ in range(args.warmup):
+        step()
+    ms_step = time_loop(step, args.steps, torch)
+    hb.hstu_profile_enable(True)
+    kern = {}
+    for _ in range(args.steps):
+        step()
+        for name, ms in hb.hstu_profile_read():
+            kern.setdefault(name, []).append(ms)
+    hb.hstu_profile_enable(False)
+    kern = {k: float(np.mean(v)) for k, v in kern.items()}
+    kept = int(new_off[-1].item())
+    row = c.width * 2
+    algo = {"truncate_fwd": 2.0 * kept * row, "truncate_bwd": float(kept + x.shape[0]) * row}
+    dom = max(algo, key=lambda k: kern[k])
+    achieved = algo[dom] / (kern[dom] * 1e-3) / 1e9
+    out = {"metric": "GB/s, jagged row selection of attention truncation (forward + backward)",
+           "value": sum(algo.values()) / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "u8", "data": "synthetic",
+           "config": {"workload": c.name, "B": len(c.lengths), "T": int(x.shape[0]), "kept_rows": kept, "keep": c.keep,
+                      "row_bytes": row},
+           "roofline": {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": achieved / PEAK_HBM_GBS, "traffic": None},
+           "kernel_ms": kern,
+           "kernel_gbs": {k: algo[k] / (kern[k] * 1e-3) / 1e9 for k in algo}}
+    if not args.no_cpu_baseline:
+        from oracle import truncation as orc
+        t0 = time.time()
+        yy, _ = orc.tail_slice(c.x, c.offsets, c.keep, None)
+        orc.tail_slice_bwd(yy, c.offsets, c.keep, None)
+        dt = time.time() - t0
+        out["cpu_baseline"] = {"value": sum(algo.values()) / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the whole batch, forward + backward, numpy row copies, {dt:.2f} s"}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (sequences shard across GPUs "
               "with no exchange in the attention path, see DESIGN.md)", file=sys.stderr)
         sys.exit(2)
+    if args.op == "truncate":
+        return bench_truncate(args)
     import torch
     from paper_2602_16986_amd import binding as hb
     from paper_2602_16986_amd import flops, workloads

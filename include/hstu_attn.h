@@ -2,8 +2,8 @@
  * hstu_attn.h - C ABI of the MI355X (gfx950) jagged HSTU attention library.
  *
  * The library computes the attention step and the gated-normalisation step of one
- * HSTU layer (paper Eq. 3 and Eq. 4) over jagged, variable-length sequences, and
- * their backward passes (op signatures of the appendix pseudocode of the paper:
+ * HSTU layer (paper Eq. 3 and Eq. 4) over jagged, variable-length sequences, their
+ * backward passes, and the jagged row selection of attention truncation (Section 4.3) (op signatures of the appendix pseudocode of the paper:
  * attention_forward(q,k,v), attention_backward(dattn,q,k,v),
  * gated_norm_forward(attn,u,w), gated_norm_backward(dy,attn,u,w)).
  *
@@ -131,6 +131,33 @@ int hstu_gated_norm_bwd(int64_t T, int32_t D, int32_t dtype, const void* dy, con
                         const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
                         float* dbeta, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Attention truncation (paper Section 4.3, "Attention Truncation"): after a first group of layers has seen
+ * the whole sequence, the remaining layers run on a segment of it, and the segment the paper settles on is
+ * the most recent part of the user's history.  Of sequence b (n_b history rows followed by
+ * M_b = num_targets[b] candidate rows) the last min(n_b, keep) history rows and all candidates survive, in
+ * order, packed sequence after sequence; dropped rows get a zero gradient.  Rows are opaque: row_bytes
+ * bytes each (any dtype, any width), consecutive rows *_stride_bytes apart.  row_bytes, the strides and the
+ * data pointers must be multiples of 16 (HSTU_ERR_SHAPE otherwise); strides >= row_bytes.
+ *
+ * hstu_truncate_offsets: out_offsets DEVICE int32[B+1] receives the offsets of the truncated batch
+ *   (num_targets DEVICE int32[B] or NULL = no candidates; keep >= 0).
+ * hstu_truncate_fwd: y row r = the r-th surviving row of x.  y has room for y_rows rows; rows at or beyond
+ *   out_offsets[B] are not written, and nothing is written beyond y_rows (a bound such as
+ *   min(T, B * (keep + max M)) is always enough).  out_offsets must come from hstu_truncate_offsets.
+ * hstu_truncate_bwd: dx [T rows] is fully overwritten: the gradient row of every surviving row, zero for
+ *   every dropped row.
+ * All three enqueue one kernel on `stream`; nothing is allocated; B = 0 or T = 0 is valid.
+ */
+int hstu_truncate_offsets(int32_t batch, int32_t keep, const int32_t* seq_offsets, const int32_t* num_targets,
+                          int32_t* out_offsets, void* stream);
+int hstu_truncate_fwd(int32_t batch, const int32_t* seq_offsets, const int32_t* out_offsets, int64_t row_bytes,
+                      const void* x, int64_t x_stride_bytes, void* y, int64_t y_stride_bytes, int64_t y_rows,
+                      void* stream);
+int hstu_truncate_bwd(int32_t batch, int64_t total_tokens, const int32_t* seq_offsets, const int32_t* out_offsets,
+                      int64_t row_bytes, const void* dy, int64_t dy_stride_bytes, void* dx, int64_t dx_stride_bytes,
+                      void* stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* hstu_status_string(int status);
 
@@ -144,7 +171,8 @@ int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, i
  * launch made by the entry points above is bracketed by HIP events on its stream (up to 16 launches
  * between two reads).  hstu_profile_read waits for those events and returns the number of entries
  * written: names[i] (static strings: "attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "gated_norm_fwd",
- * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_fwd", "schedule_bwd" [both backward lists, one launch], "bias_expand", "dbias_zero", "dbias_reduce";
+ * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_fwd", "schedule_bwd" [both backward lists, one launch], "bias_expand", "dbias_zero", "dbias_reduce",
+ * "truncate_offsets", "truncate_fwd", "truncate_bwd";
  * "attn_bwd_dkdv" includes the kernel that combines the partial sums of cut key blocks) and
  * ms[i] = elapsed milliseconds.  HOST arrays.  Not thread-safe; enable(1) creates the events once. */
 int hstu_profile_enable(int on);

@@ -64,6 +64,12 @@ def _load() -> ctypes.CDLL:
     lib.hstu_gated_norm_bwd_workspace_bytes.argtypes = [i64, i32]
     lib.hstu_gated_norm_bwd.restype = ctypes.c_int
     lib.hstu_gated_norm_bwd.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.hstu_truncate_offsets.restype = ctypes.c_int
+    lib.hstu_truncate_offsets.argtypes = [i32, i32, vp, vp, vp, vp]
+    lib.hstu_truncate_fwd.restype = ctypes.c_int
+    lib.hstu_truncate_fwd.argtypes = [i32, vp, vp, i64, vp, i64, vp, i64, i64, vp]
+    lib.hstu_truncate_bwd.restype = ctypes.c_int
+    lib.hstu_truncate_bwd.argtypes = [i32, i64, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.hstu_profile_enable.restype = ctypes.c_int
     lib.hstu_profile_enable.argtypes = [ctypes.c_int]
     lib.hstu_profile_read.restype = ctypes.c_int
@@ -74,7 +80,8 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ["hstu_attn_workspace_bytes", "hstu_attn_fwd", "hstu_attn_bwd", "hstu_gated_norm_fwd",
            "hstu_gated_norm_bwd_workspace_bytes", "hstu_gated_norm_bwd", "hstu_status_string",
-           "hstu_attn_schedule_stats", "hstu_profile_enable", "hstu_profile_read"]
+           "hstu_attn_schedule_stats", "hstu_profile_enable", "hstu_profile_read",
+           "hstu_truncate_offsets", "hstu_truncate_fwd", "hstu_truncate_bwd"]
 
 
 def status_string(status: int) -> str:
@@ -180,6 +187,48 @@ def hstu_gated_norm_bwd(dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta,
                                   workspace.numel(), _stream(stream))
     if st != HSTU_OK:
         raise HstuError(st, "hstu_gated_norm_bwd")
+
+
+def _row_geometry(t: torch.Tensor):
+    """(row bytes, row stride in bytes) of a tensor of rows (dim 0) that are contiguous inside."""
+    assert t.dim() >= 2, "expected [rows, ...]"
+    inner = int(np.prod(t.shape[1:]))
+    expect = 1
+    for size, stride in zip(reversed(t.shape[1:]), reversed(t.stride()[1:]) if t.numel() else ()):
+        assert size == 1 or stride == expect, "rows must be contiguous inside"
+        expect *= size
+    stride = t.stride(0) if t.shape[0] > 1 else inner
+    return inner * t.element_size(), stride * t.element_size()
+
+
+def hstu_truncate_offsets(seq_offsets, keep: int, num_targets, out_offsets, stream=None) -> None:
+    st = _lib.hstu_truncate_offsets(int(seq_offsets.shape[0]) - 1, int(keep), _ptr(seq_offsets), _ptr(num_targets),
+                                    _ptr(out_offsets), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_truncate_offsets")
+
+
+def hstu_truncate_fwd(seq_offsets, out_offsets, x, y, stream=None) -> None:
+    """y[r] = r-th surviving row of x; y.shape[0] is the capacity in rows."""
+    if x.shape[0] == 0 or y.shape[0] == 0:
+        return                                   # nothing survives / nowhere to put it
+    row_bytes, xs = _row_geometry(x)
+    rb2, ys = _row_geometry(y)
+    assert rb2 == row_bytes
+    st = _lib.hstu_truncate_fwd(int(seq_offsets.shape[0]) - 1, _ptr(seq_offsets), _ptr(out_offsets), row_bytes, _ptr(x), xs,
+                                _ptr(y), ys, int(y.shape[0]), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_truncate_fwd")
+
+
+def hstu_truncate_bwd(seq_offsets, out_offsets, dy, dx, stream=None) -> None:
+    """dx (all T rows) = gradient rows of the survivors, zero elsewhere."""
+    row_bytes, xs = _row_geometry(dx)
+    _, ys = _row_geometry(dy)
+    st = _lib.hstu_truncate_bwd(int(seq_offsets.shape[0]) - 1, int(dx.shape[0]), _ptr(seq_offsets), _ptr(out_offsets),
+                                row_bytes, _ptr(dy), ys, _ptr(dx), xs, _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_truncate_bwd")
 
 
 def hstu_profile_enable(on: bool) -> None:

@@ -341,4 +341,54 @@ int hstu_gated_norm_bwd(int64_t T, int32_t D, int32_t dtype, const void* dy, con
   return HSTU_OK;
 }
 
+// ---- attention truncation (Section 4.3) ------------------------------------------------------------------------
+static bool bad16(const void* ptr) { return ((uintptr_t)ptr & 15) != 0; }
+static int validate_rows(int64_t row_bytes, int64_t stride_a, int64_t stride_b) {
+  if (row_bytes < 0 || (row_bytes & 15) || (stride_a & 15) || (stride_b & 15) || stride_a < row_bytes || stride_b < row_bytes)
+    return HSTU_ERR_SHAPE;
+  return HSTU_OK;
+}
+
+int hstu_truncate_offsets(int32_t batch, int32_t keep, const int32_t* seq_offsets, const int32_t* num_targets,
+                          int32_t* out_offsets, void* stream) {
+  if (batch < 0 || keep < 0) return HSTU_ERR_SHAPE;
+  if (!seq_offsets || !out_offsets) return HSTU_ERR_NULL;
+  ProfScope ps("truncate_offsets", (hipStream_t)stream);
+  if (launch_truncate_offsets(batch, keep, seq_offsets, num_targets, out_offsets, (hipStream_t)stream) != hipSuccess)
+    return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
+int hstu_truncate_fwd(int32_t batch, const int32_t* seq_offsets, const int32_t* out_offsets, int64_t row_bytes,
+                      const void* x, int64_t x_stride_bytes, void* y, int64_t y_stride_bytes, int64_t y_rows,
+                      void* stream) {
+  if (batch < 0 || y_rows < 0) return HSTU_ERR_SHAPE;
+  const int st = validate_rows(row_bytes, x_stride_bytes, y_stride_bytes);
+  if (st != HSTU_OK) return st;
+  if (batch == 0 || y_rows == 0 || row_bytes == 0) return HSTU_OK;
+  if (!seq_offsets || !out_offsets || !x || !y) return HSTU_ERR_NULL;
+  if (bad16(x) || bad16(y)) return HSTU_ERR_SHAPE;
+  ProfScope ps("truncate_fwd", (hipStream_t)stream);
+  if (launch_truncate_gather(batch, seq_offsets, out_offsets, row_bytes, x, x_stride_bytes, y, y_stride_bytes, y_rows,
+                             (hipStream_t)stream) != hipSuccess)
+    return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
+int hstu_truncate_bwd(int32_t batch, int64_t total_tokens, const int32_t* seq_offsets, const int32_t* out_offsets,
+                      int64_t row_bytes, const void* dy, int64_t dy_stride_bytes, void* dx, int64_t dx_stride_bytes,
+                      void* stream) {
+  if (batch < 0 || total_tokens < 0 || total_tokens > 0x7fffffff) return HSTU_ERR_SHAPE;
+  const int st = validate_rows(row_bytes, dy_stride_bytes, dx_stride_bytes);
+  if (st != HSTU_OK) return st;
+  if (batch == 0 || total_tokens == 0 || row_bytes == 0) return HSTU_OK;
+  if (!seq_offsets || !out_offsets || !dx) return HSTU_ERR_NULL;   // dy may be NULL when no row survives (never read then)
+  if (bad16(dy) || bad16(dx)) return HSTU_ERR_SHAPE;
+  ProfScope ps("truncate_bwd", (hipStream_t)stream);
+  if (launch_truncate_scatter(batch, total_tokens, seq_offsets, out_offsets, row_bytes, dy, dy_stride_bytes, dx,
+                              dx_stride_bytes, (hipStream_t)stream) != hipSuccess)
+    return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
 }  // extern "C"

@@ -85,4 +85,13 @@ hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, co
                                  const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
                                  float* dbeta, float* partial, hipStream_t stream);
 
+
+// truncate.hip (strides and row sizes in bytes, multiples of 16)
+hipError_t launch_truncate_offsets(int B, int keep, const int32_t* offsets, const int32_t* num_targets, int32_t* out,
+                                   hipStream_t stream);
+hipError_t launch_truncate_gather(int B, const int32_t* offsets, const int32_t* out_offsets, int64_t row_bytes, const void* x,
+                                  int64_t x_stride, void* y, int64_t y_stride, int64_t y_rows, hipStream_t stream);
+hipError_t launch_truncate_scatter(int B, int64_t T, const int32_t* offsets, const int32_t* out_offsets, int64_t row_bytes,
+                                   const void* dy, int64_t dy_stride, void* dx, int64_t dx_stride, hipStream_t stream);
+
 }  // namespace hstu

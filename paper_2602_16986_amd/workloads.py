@@ -189,3 +189,60 @@ def small(name: str, seed: int = 0) -> Workload:
 SMALL_CASES = ["bf16-dense", "bf16-sparse", "bf16-sparse-aligned", "bf16-local-only",
                "bf16-global-only", "bf16-targets", "bf16-targets-sparse", "bf16-d64",
                "fp32-sparse", "fp32-d128"]
+
+
+# ----------------------------------------------------------------------------------------------
+# attention truncation (Section 4.3): jagged batches of opaque token rows
+# ----------------------------------------------------------------------------------------------
+@dataclasses.dataclass
+class TruncationCase:
+    name: str
+    lengths: np.ndarray          # int32 [B], history + candidates
+    offsets: np.ndarray          # int32 [B+1]
+    num_targets: Optional[np.ndarray]
+    keep: int                    # most recent history rows that survive
+    width: int                   # elements per row
+    dtype: str                   # "bf16" (stored as uint16 bit patterns), "fp32"
+    x: np.ndarray                # [T, width] rows (uint16 bits or float32)
+
+
+def truncation_case(name: str, seed: int = 0) -> TruncationCase:
+    """Seeded batches for the row selection.  "AT-3072-512" has the shape the paper reports for
+    attention truncation (sequences up to 3072 cut to their latest 512 tokens) at the batch size and
+    embedding width of its memory figures (256 sequences, 512 features, bf16); the others are small
+    cases with empty sequences, candidates, odd widths and more sequences than one scan chunk."""
+    rng = np.random.default_rng(1000 + seed)
+    nt = None
+    if name == "AT-3072-512":
+        lengths, keep, width, dtype = rng.integers(1024, 3073, 256), 512, 512, "bf16"
+    elif name == "small":
+        lengths, keep, width, dtype = np.array([5, 0, 1, 40, 17, 3, 64, 0]), 6, 8, "bf16"
+    elif name == "small-targets":
+        lengths, keep, width, dtype = np.array([50, 9, 0, 33, 21, 128]), 16, 520, "bf16"
+        nt = np.array([10, 9, 0, 0, 5, 1])
+    elif name == "small-fp32":
+        lengths, keep, width, dtype = rng.integers(0, 90, 37), 31, 12, "fp32"
+        nt = np.minimum(rng.integers(0, 8, 37), lengths)
+    elif name == "many-sequences":
+        lengths, keep, width, dtype = rng.integers(0, 24, 3001), 7, 16, "bf16"
+        nt = np.minimum(rng.integers(0, 3, 3001), lengths)
+    elif name == "empty":
+        lengths, keep, width, dtype = np.zeros(3, dtype=np.int64), 4, 8, "bf16"
+    elif name == "keep-all":
+        lengths, keep, width, dtype = rng.integers(1, 70, 12), 1 << 20, 64, "bf16"
+    elif name == "keep-none":
+        lengths, keep, width, dtype = rng.integers(1, 70, 12), 0, 64, "bf16"
+        nt = np.minimum(rng.integers(0, 4, 12), lengths)
+    else:
+        raise ValueError(f"unknown truncation case {name!r}")
+    lengths = np.asarray(lengths, dtype=np.int32)
+    offsets = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    T = int(offsets[-1])
+    if dtype == "bf16":
+        x = rng.integers(0, 1 << 16, size=(T, width), dtype=np.uint16)      # arbitrary bit patterns: rows are opaque
+    else:
+        x = rng.standard_normal((T, width)).astype(np.float32)
+    return TruncationCase(name, lengths, offsets, None if nt is None else np.asarray(nt, dtype=np.int32), keep, width, dtype, x)
+
+
+TRUNCATION_SMALL = ["small", "empty", "small-targets", "small-fp32", "many-sequences", "keep-all", "keep-none"]
