@@ -24,8 +24,10 @@ PEAK_HBM_GBS = 8000.0
 # bytes behind the L2 per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/attention_c3_dense_counters.md (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration
 # against a plain 1 GiB copy); only known for the workload that was profiled
-MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 4.696e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 5.041e9 + 0.090e9,
-                          ("C3-dense", "attn_bwd_dkdv"): 4.470e9 + 0.180e9}
+MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 4.783e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 5.024e9 + 0.090e9,
+                          ("C3-dense", "attn_bwd_dkdv"): 4.472e9 + 0.180e9,
+                          # profiles/truncation_at_3072_512.md
+                          ("AT-3072-512", "truncate_fwd"): 0.1343e9 + 0.1342e9, ("AT-3072-512", "truncate_bwd"): 0.1343e9 + 0.5240e9}
 
 
 def parse():
@@ -89,6 +91,15 @@ def cpu_baseline(w, fl, target_seconds):
                       f"{' + backward (dQ, dK, dV rows)' if w.backward else ''}, fp64, {dt:.1f} s"}
 
 
+def calibrate_copy(torch, device):
+    """One plain 1 GiB device-to-device copy: the known-size kernel the HBM byte counters are scaled by."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=device)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_truncate(args):
     """Row selection of attention truncation: offsets + gather (forward), scatter with zero fill (backward).
     Algorithmic bytes: forward reads and writes the kept rows (2 x T' x row bytes); backward reads the kept
@@ -110,6 +121,8 @@ def bench_truncate(args):
         hb.hstu_truncate_fwd(off, new_off, x, y)
         hb.hstu_truncate_bwd(off, new_off, y, dx)
 
+    if args.calibrate_copy:
+        calibrate_copy(torch, dev)
     for _ in range(args.warmup):
         step()
     ms_step = time_loop(step, args.steps, torch)
@@ -133,7 +146,7 @@ def bench_truncate(args):
            "config": {"workload": c.name, "B": len(c.lengths), "T": int(x.shape[0]), "kept_rows": kept, "keep": c.keep,
                       "row_bytes": row},
            "roofline": {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": achieved / PEAK_HBM_GBS, "traffic": None},
+                        "frac": achieved / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((c.name, dom))},
            "kernel_ms": kern,
            "kernel_gbs": {k: algo[k] / (kern[k] * 1e-3) / 1e9 for k in algo}}
     if not args.no_cpu_baseline:
@@ -172,11 +185,7 @@ def main():
             dw.attn_fwd()
 
     if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dw.device)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch, dw.device)
     for _ in range(args.warmup):
         step()
     ms_step = time_loop(step, args.steps, torch)
