@@ -246,3 +246,86 @@ def truncation_case(name: str, seed: int = 0) -> TruncationCase:
 
 
 TRUNCATION_SMALL = ["small", "empty", "small-targets", "small-fp32", "many-sequences", "keep-all", "keep-none"]
+
+
+# ----------------------------------------------------------------------------------------------
+# whole HSTU layer (Eq. 1-5 and the layer pseudocode of the appendix): token rows and weights
+# ----------------------------------------------------------------------------------------------
+@dataclasses.dataclass
+class LayerCase:
+    name: str
+    dtype: str                         # storage type of z, w1, w2, dout and every activation
+    lengths: np.ndarray
+    offsets: np.ndarray
+    num_targets: Optional[np.ndarray]
+    H: int
+    d: int
+    E: int                             # embedding width of the token rows
+    K1: int
+    K2: int
+    alpha: float
+    N: float
+    table: Optional[np.ndarray]
+    bounds: Optional[np.ndarray]
+    z: np.ndarray                      # fp32 [T, E] layer input (rounded to dtype)
+    norm_w: np.ndarray                 # fp32 [E]
+    w1: np.ndarray                     # fp32 [4 H d, E] (rounded to dtype), output order U, V, Q, K
+    gated_norm_w: np.ndarray           # fp32 [H d]
+    w2: np.ndarray                     # fp32 [E, H d] (rounded to dtype)
+    dout: np.ndarray                   # fp32 [T, E] gradient of the layer output (rounded to dtype)
+    eps: float = 1e-5
+
+    @property
+    def B(self) -> int:
+        return int(self.lengths.shape[0])
+
+    @property
+    def T(self) -> int:
+        return int(self.offsets[-1])
+
+    @property
+    def max_seqlen(self) -> int:
+        return int(self.lengths.max()) if self.B else 0
+
+
+def build_layer(name, lengths, H, d, E, dtype="bf16", *, seed=0, K1=-1, K2=0, num_targets=None, bias=True) -> LayerCase:
+    """Draw order: z, norm_w, w1, gated_norm_w, w2, table, dout.  Token rows ~ N(0, 1); weights ~ N(0, 1/fan_in) so that
+    the pre-activations are O(1); norm weights 1 + 0.1 N(0, 1); alpha = 1/sqrt(d) keeps the scores O(1)."""
+    rng = np.random.default_rng(2000 + seed)
+    lengths = np.asarray(lengths, dtype=np.int32)
+    offsets = np.zeros(lengths.shape[0] + 1, dtype=np.int32)
+    np.cumsum(lengths, out=offsets[1:])
+    T, HD = int(offsets[-1]), H * d
+    z = _normal(rng, (T, E), 1.0, dtype)
+    norm_w = (1.0 + 0.1 * rng.standard_normal(E, dtype=np.float32)).astype(np.float32)
+    w1 = _normal(rng, (4 * HD, E), 1.0 / np.sqrt(E), dtype)
+    gated_norm_w = (1.0 + 0.1 * rng.standard_normal(HD, dtype=np.float32)).astype(np.float32)
+    w2 = _normal(rng, (E, HD), 1.0 / np.sqrt(HD), dtype)
+    table = rng.standard_normal((H, NUM_BUCKETS), dtype=np.float32) * np.float32(0.1) if bias else None
+    bounds = log_bucket_bounds() if bias else None
+    dout = _normal(rng, (T, E), 1.0, dtype)
+    N = float(max(int(lengths.max()), 1)) if lengths.size else 1.0
+    nt = None if num_targets is None else np.asarray(num_targets, dtype=np.int32)
+    return LayerCase(name, dtype, lengths, offsets, nt, H, d, E, K1, K2, 1.0 / float(np.sqrt(d)), N, table, bounds, z, norm_w,
+                     w1, gated_norm_w, w2, dout)
+
+
+def layer_case(name: str, seed: int = 0) -> LayerCase:
+    """"layer-C3": the 8k-16k attention configuration inside a layer of embedding width 512 (the width of the paper's
+    memory figures, Section 4.2.2).  The others are cases the CPU oracle finishes in seconds."""
+    if name == "layer-C3":
+        L = np.random.default_rng(seed).integers(8192, 16385, size=8)      # the lengths of C3-dense
+        return build_layer(name, L, 4, 128, 512, seed=seed)
+    if name == "layer-mid":
+        L = np.random.default_rng(seed + 1).integers(1024, 2049, size=4)
+        return build_layer(name, L, 4, 128, 512, seed=seed)
+    if name == "layer-small-dense":
+        return build_layer(name, [70, 0, 33, 129], 2, 64, 96, seed=seed)
+    if name == "layer-small-sparse-targets":
+        return build_layer(name, [200, 90, 31], 2, 128, 256, seed=seed, K1=64, K2=16, num_targets=[20, 0, 30])
+    if name == "layer-small-nobias":
+        return build_layer(name, [150, 1, 300], 1, 128, 128, seed=seed, K1=100, K2=0, bias=False)
+    raise ValueError(f"unknown layer case {name!r}")
+
+
+LAYER_SMALL = ["layer-small-dense", "layer-small-sparse-targets", "layer-small-nobias"]
