@@ -158,6 +158,54 @@ int hstu_truncate_bwd(int32_t batch, int64_t total_tokens, const int32_t* seq_of
                       int64_t row_bytes, const void* dy, int64_t dy_stride_bytes, void* dx, int64_t dx_stride_bytes,
                       void* stream);
 
+/*
+ * One whole HSTU layer (paper Eq. 1-5) with the selective activation rematerialisation of Section 4.2.2
+ * (layer pseudocode of the appendix).  For token rows Z [T, E] of the jagged batch described by `attn`:
+ *   X = LayerNorm_E(Z) * norm_w                       (Eq. 1; weight only, biased variance, eps inside the root)
+ *   [U V Q K] = SiLU(X W1^T)                          (Eq. 2; W1 [4*H*d, E] row-major, rows [0, H*d) give U, then V, Q, K)
+ *   A = attention(Q, K, V)                            (Eq. 3, as hstu_attn_fwd with the mask/bias fields of `attn`)
+ *   Y = LayerNorm_{H*d}(A) * gated_norm_w (.) U       (Eq. 4 before f2, as hstu_gated_norm_fwd without beta)
+ *   out = Y W2^T + Z                                  (f2 as one linear map W2 [E, H*d] row-major, Eq. 5 residual)
+ * Only bf16 (attn.dtype = HSTU_BF16): z, out, u_saved, attn_saved, dout, dz, w1, w2 are bf16 and contiguous
+ * ([T, E] or [T, H*d]); norm_w, gated_norm_w and every weight gradient are fp32.  attn.row_stride_* are ignored
+ * (the layer places Q, K, V in one [T, 4*H*d] buffer); attn.d_rab_table, when set, receives the bias-table
+ * gradient in hstu_layer_bwd.  E: a multiple of 8, at most 8192; H*d at most 8192.
+ *
+ * The forward writes `out` and what the backward needs besides Z and the weights: u_saved [T, H*d],
+ * attn_saved [T, H*d], mean and rstd of the input norm (fp32 [T]); V, Q, K, X and Y live in the workspace
+ * and are dropped.  The backward rebuilds them (X from the saved statistics, U V Q K by the same GEMM, Y by
+ * the gated norm) and returns dz [T, E] (including the residual's share) and fp32 d_norm_w [E],
+ * d_w1 [4*H*d, E], d_gated_norm_w [H*d], d_w2 [E, H*d], all overwritten.  dU, dV, dQ, dK are written
+ * straight into the column blocks of one gradient buffer (no concatenation).
+ *
+ * The four projections run through hipBLASLt (plain library GEMMs); the first call on a device creates a
+ * hipBLASLt handle and the matmul plans, which allocate inside that library; later calls with the same shapes
+ * allocate nothing.  Not thread-safe.  HSTU_ERR_UNSUPPORTED if the library has no kernel for a shape.
+ * T = 0: the forward writes nothing, the backward zeroes the weight gradients.
+ */
+typedef struct hstu_layer_params {
+  hstu_attn_params attn;      /* the jagged batch, mask, bias and scales; see above for the ignored fields */
+  int32_t embed_dim;          /* E */
+  float norm_eps;             /* eps of the input norm */
+  float gated_norm_eps;       /* eps of the gated norm */
+  const float* norm_w;        /* DEVICE fp32[E] */
+  const void* w1;             /* DEVICE bf16 [4*H*d, E] */
+  const float* gated_norm_w;  /* DEVICE fp32[H*d] */
+  const void* w2;             /* DEVICE bf16 [E, H*d] */
+} hstu_layer_params;
+
+/* Bytes of device scratch (256-byte aligned) for hstu_layer_fwd (for_backward = 0) or hstu_layer_bwd; 0 for an
+ * invalid description.  Forward: X, the projection and Y (T*(E + 5*H*d) bf16), backward: 17 such [T, 512]-sized
+ * buffers at E = H*d = 512; both include the attention workspace and 64 MiB offered to the GEMM library. */
+size_t hstu_layer_workspace_bytes(const hstu_layer_params* p, int for_backward);
+
+int hstu_layer_fwd(const hstu_layer_params* p, const void* z, void* out, void* u_saved, void* attn_saved, float* mean,
+                   float* rstd, void* workspace, size_t workspace_bytes, void* stream);
+
+int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_saved, const void* attn_saved,
+                   const float* mean, const float* rstd, const void* dout, void* dz, float* d_norm_w, float* d_w1,
+                   float* d_gated_norm_w, float* d_w2, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* hstu_status_string(int status);
 
@@ -168,11 +216,12 @@ const char* hstu_status_string(int status);
 int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, int for_backward, int64_t out[3]);
 
 /* Per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every kernel
- * launch made by the entry points above is bracketed by HIP events on its stream (up to 16 launches
+ * launch made by the entry points above is bracketed by HIP events on its stream (up to 64 launches
  * between two reads).  hstu_profile_read waits for those events and returns the number of entries
  * written: names[i] (static strings: "attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "gated_norm_fwd",
  * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_fwd", "schedule_bwd" [both backward lists, one launch], "bias_expand", "dbias_zero", "dbias_reduce",
- * "truncate_offsets", "truncate_fwd", "truncate_bwd";
+ * "truncate_offsets", "truncate_fwd", "truncate_bwd", and from the layer entry points "layer_norm_fwd",
+ * "gemm_uvqk", "silu_fwd", "gemm_out", "gemm_dy", "gemm_dw2", "silu_bwd", "gemm_dxn", "gemm_dw1", "layer_norm_bwd";
  * "attn_bwd_dkdv" includes the kernel that combines the partial sums of cut key blocks) and
  * ms[i] = elapsed milliseconds.  HOST arrays.  Not thread-safe; enable(1) creates the events once. */
 int hstu_profile_enable(int on);

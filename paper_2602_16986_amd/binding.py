@@ -41,6 +41,14 @@ class HstuAttnParams(ctypes.Structure):
     ]
 
 
+class HstuLayerParams(ctypes.Structure):
+    _fields_ = [
+        ("attn", HstuAttnParams), ("embed_dim", ctypes.c_int32), ("norm_eps", ctypes.c_float),
+        ("gated_norm_eps", ctypes.c_float), ("norm_w", ctypes.c_void_p), ("w1", ctypes.c_void_p),
+        ("gated_norm_w", ctypes.c_void_p), ("w2", ctypes.c_void_p),
+    ]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2602_16986_amd.build` "
@@ -70,6 +78,13 @@ def _load() -> ctypes.CDLL:
     lib.hstu_truncate_fwd.argtypes = [i32, vp, vp, i64, vp, i64, vp, i64, i64, vp]
     lib.hstu_truncate_bwd.restype = ctypes.c_int
     lib.hstu_truncate_bwd.argtypes = [i32, i64, vp, vp, i64, vp, i64, vp, i64, vp]
+    lp = ctypes.POINTER(HstuLayerParams)
+    lib.hstu_layer_workspace_bytes.restype = sz
+    lib.hstu_layer_workspace_bytes.argtypes = [lp, ctypes.c_int]
+    lib.hstu_layer_fwd.restype = ctypes.c_int
+    lib.hstu_layer_fwd.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.hstu_layer_bwd.restype = ctypes.c_int
+    lib.hstu_layer_bwd.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hstu_profile_enable.restype = ctypes.c_int
     lib.hstu_profile_enable.argtypes = [ctypes.c_int]
     lib.hstu_profile_read.restype = ctypes.c_int
@@ -81,7 +96,8 @@ _lib = _load()
 EXPORTS = ["hstu_attn_workspace_bytes", "hstu_attn_fwd", "hstu_attn_bwd", "hstu_gated_norm_fwd",
            "hstu_gated_norm_bwd_workspace_bytes", "hstu_gated_norm_bwd", "hstu_status_string",
            "hstu_attn_schedule_stats", "hstu_profile_enable", "hstu_profile_read",
-           "hstu_truncate_offsets", "hstu_truncate_fwd", "hstu_truncate_bwd"]
+           "hstu_truncate_offsets", "hstu_truncate_fwd", "hstu_truncate_bwd",
+           "hstu_layer_workspace_bytes", "hstu_layer_fwd", "hstu_layer_bwd"]
 
 
 def status_string(status: int) -> str:
@@ -231,13 +247,65 @@ def hstu_truncate_bwd(seq_offsets, out_offsets, dy, dx, stream=None) -> None:
         raise HstuError(st, "hstu_truncate_bwd")
 
 
+class LayerProblem:
+    """Owns an ``hstu_layer_params`` struct (bf16 layer) and keeps the tensors it points to alive."""
+
+    def __init__(self, *, num_heads, head_dim, embed_dim, total_tokens, seq_offsets, max_seqlen, norm_w, w1, gated_norm_w,
+                 w2, num_targets=None, local_window=-1, global_prefix=0, alpha=1.0, inv_n=1.0, rab_table=None,
+                 rab_bounds=None, d_rab_table=None, norm_eps=1e-5, gated_norm_eps=1e-5):
+        hd = num_heads * head_dim
+        assert w1.dtype == torch.bfloat16 and w2.dtype == torch.bfloat16 and w1.is_contiguous() and w2.is_contiguous()
+        assert tuple(w1.shape) == (4 * hd, embed_dim) and tuple(w2.shape) == (embed_dim, hd)
+        assert norm_w.dtype == torch.float32 and gated_norm_w.dtype == torch.float32
+        self._keep = (seq_offsets, num_targets, rab_table, rab_bounds, d_rab_table, norm_w, w1, gated_norm_w, w2)
+        p = HstuLayerParams()
+        a = p.attn
+        a.batch = int(seq_offsets.shape[0]) - 1
+        a.num_heads, a.head_dim, a.total_tokens, a.max_seqlen = num_heads, head_dim, int(total_tokens), int(max_seqlen)
+        a.dtype = HSTU_BF16
+        a.row_stride_q = a.row_stride_k = a.row_stride_v = 4 * hd      # ignored by the layer entry points
+        a.row_stride_o = hd
+        a.seq_offsets, a.seq_offsets_host, a.num_targets = _ptr(seq_offsets), None, _ptr(num_targets)
+        a.local_window, a.global_prefix = int(local_window), int(global_prefix)
+        a.alpha, a.inv_n = float(alpha), float(inv_n)
+        a.rab_table, a.rab_bounds = _ptr(rab_table), _ptr(rab_bounds)
+        a.num_buckets = 0 if rab_bounds is None else int(rab_bounds.shape[0])
+        a.d_rab_table = _ptr(d_rab_table)
+        p.embed_dim, p.norm_eps, p.gated_norm_eps = int(embed_dim), float(norm_eps), float(gated_norm_eps)
+        p.norm_w, p.w1, p.gated_norm_w, p.w2 = _ptr(norm_w), _ptr(w1), _ptr(gated_norm_w), _ptr(w2)
+        self.params = p
+
+    def ref(self):
+        return ctypes.byref(self.params)
+
+
+def hstu_layer_workspace_bytes(prob: LayerProblem, for_backward: bool) -> int:
+    return int(_lib.hstu_layer_workspace_bytes(prob.ref(), 1 if for_backward else 0))
+
+
+def hstu_layer_fwd(prob: LayerProblem, z, out, u_saved, attn_saved, mean, rstd, workspace, stream=None) -> None:
+    st = _lib.hstu_layer_fwd(prob.ref(), _ptr(z), _ptr(out), _ptr(u_saved), _ptr(attn_saved), _ptr(mean), _ptr(rstd),
+                             _ptr(workspace), workspace.numel(), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_layer_fwd")
+
+
+def hstu_layer_bwd(prob: LayerProblem, z, u_saved, attn_saved, mean, rstd, dout, dz, d_norm_w, d_w1, d_gated_norm_w, d_w2,
+                   workspace, stream=None) -> None:
+    st = _lib.hstu_layer_bwd(prob.ref(), _ptr(z), _ptr(u_saved), _ptr(attn_saved), _ptr(mean), _ptr(rstd), _ptr(dout),
+                             _ptr(dz), _ptr(d_norm_w), _ptr(d_w1), _ptr(d_gated_norm_w), _ptr(d_w2), _ptr(workspace),
+                             workspace.numel(), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_layer_bwd")
+
+
 def hstu_profile_enable(on: bool) -> None:
     st = _lib.hstu_profile_enable(1 if on else 0)
     if st != HSTU_OK:
         raise HstuError(st, "hstu_profile_enable")
 
 
-def hstu_profile_read(max_entries: int = 16):
+def hstu_profile_read(max_entries: int = 64):
     """[(kernel name, milliseconds)] for the launches since the last read; waits for them to finish."""
     names = (ctypes.c_char_p * max_entries)()
     ms = (ctypes.c_float * max_entries)()

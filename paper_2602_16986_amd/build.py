@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhstu_attn.so")
-SOURCES = ["api.hip", "schedule.hip", "attn_core.hip", "gated_norm.hip", "truncate.hip"]
+SOURCES = ["api.hip", "schedule.hip", "attn_core.hip", "gated_norm.hip", "truncate.hip", "pointwise.hip", "gemm.hip", "layer.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          # packed fp32 VALU forms are kept off on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -34,7 +34,7 @@ def build_library(verbose: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=4) as pool:
         objs = list(pool.map(lambda s: _compile(s, objdir), SOURCES))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs, "-lhipblaslt"]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stderr)

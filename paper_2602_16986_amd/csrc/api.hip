@@ -3,6 +3,7 @@
 #include "../../include/hstu_attn.h"
 #include "hstu_common.h"
 #include "hstu_kernels.h"
+#include "profile.h"
 
 using namespace hstu;
 
@@ -116,27 +117,28 @@ hipError_t prepare_bias(const hstu_attn_params* p, AttnArgs& a, unsigned char* w
   return launch_bias_expand(p->rab_table, p->rab_bounds, p->num_buckets, p->num_heads, a.bias_stride, bias, stream);
 }
 
+}  // namespace
+
 // ---- optional per-kernel timing (for benchmarks): HIP events around every launch, on the launch stream
-constexpr int kProfSlots = 16;
+namespace hstu {
+constexpr int kProfSlots = 64;
 struct ProfSlot { const char* name; hipEvent_t e0, e1; bool used; };
-ProfSlot g_prof[kProfSlots];
-bool g_prof_on = false, g_prof_init = false;
-int g_prof_n = 0;
+static ProfSlot g_prof[kProfSlots];
+static bool g_prof_on = false, g_prof_init = false;
+static int g_prof_n = 0;
 
-struct ProfScope {
-  ProfSlot* s;
-  hipStream_t stream;
-  ProfScope(const char* name, hipStream_t st) : s(nullptr), stream(st) {
-    if (!g_prof_on || g_prof_n >= kProfSlots) return;
-    s = &g_prof[g_prof_n++];
-    s->name = name;
-    s->used = hipEventRecord(s->e0, stream) == hipSuccess;
-  }
-  ~ProfScope() {
-    if (s && s->used) s->used = hipEventRecord(s->e1, stream) == hipSuccess;
-  }
-};
+ProfScope::ProfScope(const char* name, hipStream_t st) : s(nullptr), stream(st) {
+  if (!g_prof_on || g_prof_n >= kProfSlots) return;
+  s = &g_prof[g_prof_n++];
+  s->name = name;
+  s->used = hipEventRecord(s->e0, stream) == hipSuccess;
+}
+ProfScope::~ProfScope() {
+  if (s && s->used) s->used = hipEventRecord(s->e1, stream) == hipSuccess;
+}
+}  // namespace hstu
 
+namespace {
 }  // namespace
 
 extern "C" {

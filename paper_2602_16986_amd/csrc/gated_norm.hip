@@ -68,18 +68,14 @@ __device__ __forceinline__ void row_stats(const float (&a)[NCH][8], int lane, in
 }
 
 template <typename E, int NCH>
-__global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_fwd_kernel(int64_t T, int D, const E* __restrict__ attn,
-                                                                            const E* __restrict__ u,
-                                                                            const float* __restrict__ gamma,
-                                                                            const float* __restrict__ beta, float eps,
-                                                                            E* __restrict__ y, float* __restrict__ mean,
-                                                                            float* __restrict__ rstd) {
+__global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_fwd_kernel(const NormFwdArgs p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave;
-  if (row >= T) return;
-  const E* arow = attn + row * D;
-  const E* urow = u + row * D;
-  E* yrow = y + row * D;
+  const int D = p.D;
+  if (row >= p.T) return;
+  const E* arow = (const E*)p.a + row * p.sa;
+  const E* urow = p.u ? (const E*)p.u + row * p.su : nullptr;       // no gate: plain layer norm
+  E* yrow = (E*)p.y + row * p.sy;
   float a[NCH][8];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
@@ -87,23 +83,27 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_fwd_kernel(int6
     if (e0 < D) load8(arow, e0, a[c]);
   }
   float mu, rs;
-  row_stats<NCH>(a, lane, D, eps, mu, rs);
+  if (p.stats_in) { mu = p.mean[row]; rs = p.rstd[row]; }           // statistics saved by an earlier pass
+  else row_stats<NCH>(a, lane, D, p.eps, mu, rs);
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int e0 = (lane + 64 * c) * 8;
     if (e0 < D) {
       float uv[8], gv[8], bv[8], out[8];
-      load8(urow, e0, uv);
-      load8(gamma, e0, gv);
-      if (beta) load8(beta, e0, bv);
+      if (urow) load8(urow, e0, uv);
+      load8(p.gamma, e0, gv);
+      if (p.beta) load8(p.beta, e0, bv);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) out[i] = ((a[c][i] - mu) * rs * gv[i] + (beta ? bv[i] : 0.f)) * uv[i];
+      for (int i = 0; i < 8; ++i) {
+        out[i] = (a[c][i] - mu) * rs * gv[i] + (p.beta ? bv[i] : 0.f);
+        if (urow) out[i] *= uv[i];
+      }
       store8(yrow, e0, out);
     }
   }
-  if (lane == 0) {
-    if (mean) mean[row] = mu;
-    if (rstd) rstd[row] = rs;
+  if (lane == 0 && !p.stats_in) {
+    if (p.mean) p.mean[row] = mu;
+    if (p.rstd) p.rstd[row] = rs;
   }
 }
 
@@ -112,15 +112,12 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_fwd_kernel(int6
 // dbeta = sum dn are kept per lane over the rows a wave visits, combined across the workgroup's
 // waves in a fixed order through LDS and written as one partial row per workgroup.
 template <typename E, int NCH>
-__global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(int64_t T, int D, const E* __restrict__ dy,
-                                                                            const E* __restrict__ attn,
-                                                                            const E* __restrict__ u,
-                                                                            const float* __restrict__ gamma,
-                                                                            const float* __restrict__ beta, float eps,
-                                                                            E* __restrict__ dattn, E* __restrict__ du,
-                                                                            float* __restrict__ partial) {
+__global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(const NormBwdArgs p, float* __restrict__ partial) {
   extern __shared__ float red[];                       // [2][D]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int D = p.D;
+  const float* __restrict__ gamma = p.gamma;
+  const float* __restrict__ beta = p.beta;
   float gsum[NCH][8], bsum[NCH][8], gv[NCH][8], bv[NCH][8];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
@@ -133,8 +130,11 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(int64_t 
     }
   }
   const int64_t stride = (int64_t)gridDim.x * kBwdWaves;
-  for (int64_t row = (int64_t)blockIdx.x * kBwdWaves + wave; row < T; row += stride) {
-    const E* arow = attn + row * D;
+  for (int64_t row = (int64_t)blockIdx.x * kBwdWaves + wave; row < p.T; row += stride) {
+    const E* arow = (const E*)p.a + row * p.sa;
+    const E* dyrow = (const E*)p.dy + row * p.sdy;
+    const E* urow = p.u ? (const E*)p.u + row * p.su : nullptr;         // no gate: plain layer norm, no dU
+    const E* rrow = p.residual ? (const E*)p.residual + row * p.sres : nullptr;
     float a[NCH][8];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(int64_t 
       if (e0 < D) load8(arow, e0, a[c]);
     }
     float mu, rs;
-    row_stats<NCH>(a, lane, D, eps, mu, rs);
+    row_stats<NCH>(a, lane, D, p.eps, mu, rs);
     float m1 = 0.f, m2 = 0.f;
     float dah[NCH][8];
 #pragma unroll
@@ -150,12 +150,12 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(int64_t 
       const int e0 = (lane + 64 * c) * 8;
       if (e0 < D) {
         float dyv[8], uv[8], duv[8];
-        load8(dy + row * D, e0, dyv);
-        load8(u + row * D, e0, uv);
+        load8(dyrow, e0, dyv);
+        if (urow) load8(urow, e0, uv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float ah = (a[c][i] - mu) * rs;
-          const float dn = dyv[i] * uv[i];
+          const float dn = urow ? dyv[i] * uv[i] : dyv[i];
           duv[i] = dyv[i] * (ah * gv[c][i] + bv[c][i]);
           gsum[c][i] += dn * ah;
           bsum[c][i] += dn;
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(int64_t 
           m2 += dah[c][i] * ah;
           a[c][i] = ah;
         }
-        store8(du + row * D, e0, duv);
+        if (urow) store8((E*)p.du + row * p.sdu, e0, duv);
       }
     }
     m1 = wave_sum(m1) / (float)D;
@@ -173,10 +173,14 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(int64_t 
     for (int c = 0; c < NCH; ++c) {
       const int e0 = (lane + 64 * c) * 8;
       if (e0 < D) {
-        float dav[8];
+        float dav[8], rv[8];
+        if (rrow) load8(rrow, e0, rv);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) dav[i] = rs * (dah[c][i] - m1 - a[c][i] * m2);
-        store8(dattn + row * D, e0, dav);
+        for (int i = 0; i < 8; ++i) {
+          dav[i] = rs * (dah[c][i] - m1 - a[c][i] * m2);
+          if (rrow) dav[i] += rv[i];                   // gradient that bypasses the norm (residual connection)
+        }
+        store8((E*)p.da + row * p.sda, e0, dav);
       }
     }
   }
@@ -227,31 +231,26 @@ int gated_norm_bwd_blocks(int64_t T) {
 }
 
 template <typename E, int NCH>
-static hipError_t fwd_one(int64_t T, int D, const void* attn, const void* u, const float* gamma, const float* beta,
-                          float eps, void* y, float* mean, float* rstd, hipStream_t stream) {
-  const unsigned grid = (unsigned)((T + kRowsPerBlock - 1) / kRowsPerBlock);
-  hipLaunchKernelGGL((gated_norm_fwd_kernel<E, NCH>), dim3(grid), dim3(64 * kRowsPerBlock), 0, stream, T, D,
-                     (const E*)attn, (const E*)u, gamma, beta, eps, (E*)y, mean, rstd);
+static hipError_t fwd_one(const NormFwdArgs& p, hipStream_t stream) {
+  const unsigned grid = (unsigned)((p.T + kRowsPerBlock - 1) / kRowsPerBlock);
+  hipLaunchKernelGGL((gated_norm_fwd_kernel<E, NCH>), dim3(grid), dim3(64 * kRowsPerBlock), 0, stream, p);
   return hipGetLastError();
 }
 
 template <typename E, int NCH>
-static hipError_t bwd_one(int64_t T, int D, const void* dy, const void* attn, const void* u, const float* gamma,
-                          const float* beta, float eps, void* dattn, void* du, float* dgamma, float* dbeta,
-                          float* partial, hipStream_t stream) {
-  const int nblk = gated_norm_bwd_blocks(T);
+static hipError_t bwd_one(const NormBwdArgs& p, float* partial, hipStream_t stream) {
+  const int nblk = gated_norm_bwd_blocks(p.T);
   auto kern = gated_norm_bwd_kernel<E, NCH>;
-  const size_t smem = (size_t)2 * D * sizeof(float);
+  const size_t smem = (size_t)2 * p.D * sizeof(float);
   if (smem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(kern, dim3(nblk), dim3(64 * kBwdWaves), smem, stream, T, D, (const E*)dy, (const E*)attn,
-                     (const E*)u, gamma, beta, eps, (E*)dattn, (E*)du, partial);
+  hipLaunchKernelGGL(kern, dim3(nblk), dim3(64 * kBwdWaves), smem, stream, p, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(gated_norm_colsum_kernel, dim3((2 * D + 63) / 64), dim3(1024), 0, stream, nblk, D, partial,
-                     dgamma, dbeta);
+  hipLaunchKernelGGL(gated_norm_colsum_kernel, dim3((2 * p.D + 63) / 64), dim3(1024), 0, stream, nblk, p.D, partial,
+                     p.dgamma, p.dbeta);
   return hipGetLastError();
 }
 
@@ -262,11 +261,10 @@ static int chunks_per_lane(int D) {
   return nch;
 }
 
-hipError_t launch_gated_norm_fwd(int64_t T, int D, int dtype, const void* attn, const void* u, const float* gamma,
-                                 const float* beta, float eps, void* y, float* mean, float* rstd, hipStream_t stream) {
-  const int nch = chunks_per_lane(D);
-#define FWD_CALL(E, N) fwd_one<E, N>(T, D, attn, u, gamma, beta, eps, y, mean, rstd, stream)
-  if (dtype == 0) {
+hipError_t launch_norm_fwd(const NormFwdArgs& p, hipStream_t stream) {
+  const int nch = chunks_per_lane(p.D);
+#define FWD_CALL(E, N) fwd_one<E, N>(p, stream)
+  if (p.dtype == 0) {
     switch (nch) {
       case 1: return FWD_CALL(__bf16, 1);
       case 2: return FWD_CALL(__bf16, 2);
@@ -285,12 +283,10 @@ hipError_t launch_gated_norm_fwd(int64_t T, int D, int dtype, const void* attn, 
 #undef FWD_CALL
 }
 
-hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, const void* attn, const void* u,
-                                 const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
-                                 float* dbeta, float* partial, hipStream_t stream) {
-  const int nch = chunks_per_lane(D);
-#define BWD_CALL(E, N) bwd_one<E, N>(T, D, dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta, partial, stream)
-  if (dtype == 0) {
+hipError_t launch_norm_bwd(const NormBwdArgs& p, float* partial, hipStream_t stream) {
+  const int nch = chunks_per_lane(p.D);
+#define BWD_CALL(E, N) bwd_one<E, N>(p, partial, stream)
+  if (p.dtype == 0) {
     switch (nch) {
       case 1: return BWD_CALL(__bf16, 1);
       case 2: return BWD_CALL(__bf16, 2);
@@ -307,6 +303,25 @@ hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, co
     default: return BWD_CALL(float, 16);
   }
 #undef BWD_CALL
+}
+
+// contiguous [T, D] tensors, statistics computed: the form behind the C entry points
+hipError_t launch_gated_norm_fwd(int64_t T, int D, int dtype, const void* attn, const void* u, const float* gamma,
+                                 const float* beta, float eps, void* y, float* mean, float* rstd, hipStream_t stream) {
+  NormFwdArgs p = {};
+  p.T = T; p.D = D; p.dtype = dtype; p.a = attn; p.sa = D; p.u = u; p.su = D; p.gamma = gamma; p.beta = beta; p.eps = eps;
+  p.y = y; p.sy = D; p.mean = mean; p.rstd = rstd; p.stats_in = 0;
+  return launch_norm_fwd(p, stream);
+}
+
+hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, const void* attn, const void* u,
+                                 const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
+                                 float* dbeta, float* partial, hipStream_t stream) {
+  NormBwdArgs p = {};
+  p.T = T; p.D = D; p.dtype = dtype; p.dy = dy; p.sdy = D; p.a = attn; p.sa = D; p.u = u; p.su = D; p.gamma = gamma;
+  p.beta = beta; p.eps = eps; p.da = dattn; p.sda = D; p.du = du; p.sdu = D; p.residual = nullptr; p.sres = D;
+  p.dgamma = dgamma; p.dbeta = dbeta;
+  return launch_norm_bwd(p, partial, stream);
 }
 
 }  // namespace hstu

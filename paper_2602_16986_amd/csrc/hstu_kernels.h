@@ -78,6 +78,31 @@ hipError_t launch_dbias_reduce(const float* dist, const int32_t* bounds, int num
 hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream);
 
 // gated_norm.hip
+// Row-wise layer norm with weight (and optional bias), optionally gated by U; row strides in elements.
+struct NormFwdArgs {
+  int64_t T; int32_t D; int32_t dtype;
+  const void* a; int64_t sa;                // input rows
+  const void* u; int64_t su;                // gate, or nullptr: plain layer norm
+  const float* gamma; const float* beta;    // beta may be nullptr
+  float eps;
+  void* y; int64_t sy;
+  float* mean; float* rstd;                 // outputs (may be nullptr), or inputs when stats_in is set
+  int32_t stats_in;
+};
+struct NormBwdArgs {
+  int64_t T; int32_t D; int32_t dtype;
+  const void* dy; int64_t sdy;
+  const void* a; int64_t sa;
+  const void* u; int64_t su;                // nullptr: plain layer norm (du is not written)
+  const float* gamma; const float* beta;
+  float eps;
+  void* da; int64_t sda;
+  void* du; int64_t sdu;
+  const void* residual; int64_t sres;       // optional rows added to da (gradient of a residual connection)
+  float* dgamma; float* dbeta;              // dbeta may be nullptr
+};
+hipError_t launch_norm_fwd(const NormFwdArgs& p, hipStream_t stream);
+hipError_t launch_norm_bwd(const NormBwdArgs& p, float* partial, hipStream_t stream);   // partial: gated_norm_bwd_blocks(T) x 2 x D floats
 int gated_norm_bwd_blocks(int64_t T);
 hipError_t launch_gated_norm_fwd(int64_t T, int D, int dtype, const void* attn, const void* u, const float* gamma,
                                  const float* beta, float eps, void* y, float* mean, float* rstd, hipStream_t stream);
@@ -85,6 +110,18 @@ hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, co
                                  const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
                                  float* dbeta, float* partial, hipStream_t stream);
 
+
+// pointwise.hip: SiLU of the [T, C] projection (bf16, contiguous, C a multiple of 8) and its backward
+hipError_t launch_silu_fwd(int64_t T, int C, const void* pre, void* act, void* u_out, int u_cols, hipStream_t stream);
+hipError_t launch_silu_bwd(int64_t T, int C, const void* pre, void* dact, hipStream_t stream);
+
+// gemm.hip: row-major bf16 products with fp32 accumulation through hipBLASLt.
+//   kGemmNT: D[M,N] = A[M,K] B[N,K]^T    kGemmNN: D[M,N] = A[M,K] B[K,N]    kGemmTN: D[M,N] = A[K,M]^T B[K,N]
+// C: optional bf16 [M,N] added to the product (nullptr: none); D bf16 or fp32 (d_fp32); ld*: row strides in elements.
+// Returns 0, -1 (library error) or -2 (no kernel for this problem).
+enum { kGemmNT = 0, kGemmNN = 1, kGemmTN = 2 };
+int gemm_bf16(int op, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, const void* C,
+              int64_t ldc, void* D, int64_t ldd, bool d_fp32, void* ws, size_t ws_bytes, hipStream_t stream);
 
 // truncate.hip (strides and row sizes in bytes, multiples of 16)
 hipError_t launch_truncate_offsets(int B, int keep, const int32_t* offsets, const int32_t* num_targets, int32_t* out,

@@ -91,3 +91,53 @@ class DeviceWorkload:
         self.norm_fwd(stream=stream)
         self.norm_bwd(stream=stream)
         self.attn_bwd(dout=self.dattn, stream=stream)
+
+
+class DeviceLayer:
+    """Device-resident copy of a LayerCase (token rows, weights) plus the buffers of hstu_layer_fwd / hstu_layer_bwd."""
+
+    def __init__(self, c, device="cuda:0", bias_grad: bool = False):
+        assert c.dtype == "bf16"
+        self.c = c
+        self.device = dev = torch.device(device)
+        HD = c.H * c.d
+        self.z, self.w1, self.w2, self.dout = (_dev(x, "bf16", dev) for x in (c.z, c.w1, c.w2, c.dout))
+        self.norm_w = torch.from_numpy(c.norm_w).to(dev)
+        self.gated_norm_w = torch.from_numpy(c.gated_norm_w).to(dev)
+        self.offsets = torch.from_numpy(c.offsets).to(dev)
+        self.num_targets = None if c.num_targets is None else torch.from_numpy(c.num_targets).to(dev)
+        self.table = None if c.table is None else torch.from_numpy(c.table).to(dev)
+        self.bounds = None if c.bounds is None else torch.from_numpy(c.bounds).to(dev)
+        self.dtable = torch.empty_like(self.table) if (bias_grad and self.table is not None) else None
+        # forward outputs: the layer output and the tensors saved for the backward
+        self.out = torch.empty_like(self.z)
+        self.u_saved = torch.empty(c.T, HD, dtype=torch.bfloat16, device=dev)
+        self.attn_saved = torch.empty(c.T, HD, dtype=torch.bfloat16, device=dev)
+        self.mean = torch.empty(c.T, dtype=torch.float32, device=dev)
+        self.rstd = torch.empty(c.T, dtype=torch.float32, device=dev)
+        # backward outputs
+        self.dz = torch.empty_like(self.z)
+        self.d_norm_w = torch.empty(c.E, dtype=torch.float32, device=dev)
+        self.d_w1 = torch.empty(4 * HD, c.E, dtype=torch.float32, device=dev)
+        self.d_gated_norm_w = torch.empty(HD, dtype=torch.float32, device=dev)
+        self.d_w2 = torch.empty(c.E, HD, dtype=torch.float32, device=dev)
+        self.problem = hb.LayerProblem(num_heads=c.H, head_dim=c.d, embed_dim=c.E, total_tokens=c.T, seq_offsets=self.offsets,
+                                       max_seqlen=c.max_seqlen, norm_w=self.norm_w, w1=self.w1, gated_norm_w=self.gated_norm_w,
+                                       w2=self.w2, num_targets=self.num_targets, local_window=c.K1, global_prefix=c.K2,
+                                       alpha=c.alpha, inv_n=1.0 / c.N, rab_table=self.table, rab_bounds=self.bounds,
+                                       d_rab_table=self.dtable, norm_eps=c.eps, gated_norm_eps=c.eps)
+        self.ws_fwd = hb.new_workspace(hb.hstu_layer_workspace_bytes(self.problem, False), dev)
+        self.ws_bwd = hb.new_workspace(hb.hstu_layer_workspace_bytes(self.problem, True), dev)
+
+    def fwd(self, stream=None):
+        hb.hstu_layer_fwd(self.problem, self.z, self.out, self.u_saved, self.attn_saved, self.mean, self.rstd, self.ws_fwd, stream)
+        return self.out
+
+    def bwd(self, stream=None):
+        hb.hstu_layer_bwd(self.problem, self.z, self.u_saved, self.attn_saved, self.mean, self.rstd, self.dout, self.dz,
+                          self.d_norm_w, self.d_w1, self.d_gated_norm_w, self.d_w2, self.ws_bwd, stream)
+        return self.dz, self.d_norm_w, self.d_w1, self.d_gated_norm_w, self.d_w2
+
+    def step(self, stream=None):
+        self.fwd(stream)
+        self.bwd(stream)
