@@ -42,9 +42,13 @@ def parse():
     ap.add_argument("--fwd-only", action="store_true", help="time the forward attention only (profiling aid)")
     ap.add_argument("--bias-grad", action="store_true",
                     help="also compute the gradient of the relative-bias table in the attention backward")
-    ap.add_argument("--op", default="attention", choices=["attention", "truncate"],
+    ap.add_argument("--op", default="attention", choices=["attention", "truncate", "layer"],
                     help="attention: the hot path (default).  truncate: the row selection of attention truncation "
-                         "(Section 4.3) on the AT-3072-512 batch, forward + backward, in GB/s against the HBM roofline")
+                         "(Section 4.3) on the AT-3072-512 batch, forward + backward, in GB/s against the HBM roofline.  "
+                         "layer: one whole HSTU layer with rematerialisation (hstu_layer_fwd + hstu_layer_bwd) on layer-C3")
+    ap.add_argument("--layer-case", default="layer-C3", help="layer workload for --op layer (layer-C3, layer-mid, ...)")
+    ap.add_argument("--fused-qkvu", action="store_true",
+                    help="attention op: Q, K, V, U as column blocks of one [T, 4*H*d] buffer (row stride 4x) instead of four tensors")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (profiling aid: calibrates the HBM byte counters)")
     return ap.parse_args()
@@ -160,6 +164,55 @@ def bench_truncate(args):
     print(json.dumps(out))
 
 
+def bench_layer(args):
+    """One whole layer, forward + backward with rematerialisation.  Useful FLOPs: attention 4 d + 10 d per unmasked
+    pair and head, projections 2 M N K each forward and twice that backward (the rematerialised U/V/Q/K GEMM of the
+    backward is executed but not counted)."""
+    import torch
+    from paper_2602_16986_amd import binding as hb
+    from paper_2602_16986_amd import flops, workloads
+    from paper_2602_16986_amd.runner import DeviceLayer
+    c = workloads.layer_case(args.layer_case)
+    dl = DeviceLayer(c)
+    HD = c.H * c.d
+    fl = flops.attention_flops(c)
+    gemm_fwd = 2.0 * c.T * c.E * 4 * HD + 2.0 * c.T * HD * c.E
+    useful = fl["fwd"] + fl["bwd"] + 3.0 * gemm_fwd
+    for _ in range(args.warmup):
+        dl.step()
+    ms_step = time_loop(dl.step, args.steps, torch)
+    parts = {"layer_fwd": time_loop(dl.fwd, args.steps, torch), "layer_bwd": time_loop(dl.bwd, args.steps, torch)}
+    hb.hstu_profile_enable(True)
+    kern = {}
+    for _ in range(args.steps):
+        for tag, fn in (("fwd", dl.fwd), ("bwd", dl.bwd)):
+            fn()
+            for name, ms in hb.hstu_profile_read():
+                kern.setdefault(f"{tag}:{name}", []).append(ms)
+    hb.hstu_profile_enable(False)
+    kern = {k: float(np.mean(v)) for k, v in kern.items()}
+    algo = {"fwd:attn_fwd": 4.0, "bwd:attn_bwd_dq": 6.0, "bwd:attn_bwd_dkdv": 8.0}
+    dom = max(algo, key=lambda k: kern[k])
+    achieved = algo[dom] * c.d * fl["pairs"] / (kern[dom] * 1e-3) / 1e12
+    e = 2 * c.T
+    out = {"metric": "useful TFLOP/s, one HSTU layer forward + backward with activation rematerialisation",
+           "value": useful / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": c.name, "B": c.B, "T": c.T, "H": c.H, "d": c.d, "E": c.E, "K1": c.K1, "K2": c.K2,
+                      "unmasked_pairs": fl["pairs"]},
+           "frac_of_peak": useful / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "roofline": {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
+           "entry_ms": parts, "kernel_ms": kern,
+           "attention_share_of_step": (kern["fwd:attn_fwd"] + kern["bwd:attn_bwd_dq"] + kern["bwd:attn_bwd_dkdv"]) / ms_step,
+           # activations that live from the forward to the backward, with and without rematerialisation (Section 4.2.2):
+           # kept: Z, U, A and two statistics per row; otherwise also X, V, Q, K, Y and the pre-activations
+           "saved_bytes": {"rematerialised": e * (c.E + 2 * HD) + 8 * c.T,
+                           "everything_kept": e * (2 * c.E + 4 * HD + 4 * HD + 2 * HD) + 8 * c.T}}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -168,6 +221,8 @@ def main():
         sys.exit(2)
     if args.op == "truncate":
         return bench_truncate(args)
+    if args.op == "layer":
+        return bench_layer(args)
     import torch
     from paper_2602_16986_amd import binding as hb
     from paper_2602_16986_amd import flops, workloads
@@ -175,7 +230,7 @@ def main():
 
     w = workloads.config(args.workload)
     fl = flops.attention_flops(w)
-    dw = DeviceWorkload(w, bias_grad=args.bias_grad)
+    dw = DeviceWorkload(w, bias_grad=args.bias_grad, fused_qkvu=args.fused_qkvu)
     do_bwd = w.backward and not args.fwd_only
 
     def step():

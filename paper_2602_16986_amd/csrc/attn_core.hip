@@ -11,8 +11,8 @@
 //   dK/dV     keys (K, V)       queries(Q,dO)  S   = Q K^T, dP   = dO V^T               dK^T += Q^T  dS,  dV^T += dO^T P
 //
 // with  S = alpha QK^T + bias,  P = S sigmoid(S),  dS = dP sigmoid(S) (1 + S (1 - sigmoid(S)))  under the mask
-// (paper Eq. 3 and its derivative; the 1/N and alpha factors are applied once to the
-// accumulators at the end).  There is no softmax: no running max, no row sum, no rescale.
+// (paper Eq. 3 and its derivative; alpha rides on the stationary operand of the score product, and the
+// 1/N factor, with the alpha that dQ and dK owe, is applied once to the accumulators at the end).  There is no softmax: no running max, no row sum, no rescale.
 //
 // Mapping to CDNA4 matrix cores (wave64, v_mfma_f32_32x32x16_bf16): a wave owns 32 stationary
 // rows, which sit on the lane axis of every product.  The stationary operands stay in
@@ -183,6 +183,9 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   if (C::NRES == 2) R2 += seq0 * sr2 + hoff;
 
   // ---- resident operands (B operands: lane = row x, registers = 8 (bf16) or 1 (fp32) features per k-step)
+  // The operand of the score product carries alpha log2 e: the accumulator then holds (alpha q.k) log2 e, to which the
+  // bias (already in those units) is added or with which it is seeded, for any alpha.
+  const float score_scale = kLog2e * a.alpha;
   RFrag res[C::NRES][C::KS];
 #pragma unroll
   for (int i = 0; i < C::NREG; ++i) {
@@ -192,15 +195,15 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
       if constexpr (C::kBf16) {
         u32x4 raw = {0u, 0u, 0u, 0u};
         if (x_ok) raw = *(const u32x4*)(rp + ks * 16 + hf * 8);
-        if (i == 0) {                                                    // operand of the score product: times log2 e
+        if (i == 0) {                                                    // operand of the score product
 #pragma unroll
           for (int w = 0; w < 4; ++w)
-            raw[w] = pack_bf16x2(__builtin_bit_cast(float, raw[w] << 16) * kLog2e,
-                                 __builtin_bit_cast(float, raw[w] & 0xFFFF0000u) * kLog2e);
+            raw[w] = pack_bf16x2(__builtin_bit_cast(float, raw[w] << 16) * score_scale,
+                                 __builtin_bit_cast(float, raw[w] & 0xFFFF0000u) * score_scale);
         }
         res[i][ks] = __builtin_bit_cast(RFrag, raw);
       } else {
-        res[i][ks] = x_ok ? rp[2 * ks + hf] * (i == 0 ? kLog2e : 1.0f) : 0.f;
+        res[i][ks] = x_ok ? rp[2 * ks + hf] * (i == 0 ? score_scale : 1.0f) : 0.f;
       }
     }
   }
@@ -224,7 +227,6 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   const TileRanges tr = (MODE == kBwdDKDV) ? row_tile_ranges(g, x0, xlast, C::BN) : tile_ranges(g, x0, xlast, C::BN);
   const int ntiles = min(tr.count(), item.t1);             // this item's share of the block's tile list is [t_begin, ntiles)
   const float* bias_h = a.bias ? a.bias + (int64_t)h * a.bias_stride : nullptr;
-  const bool unit_alpha = a.alpha == 1.0f;
   // this lane's start inside the bias strip: copy c = s0 mod 4 makes its 4-entry reads 16-byte aligned
   const int strip_s0 = C::BX - 1 - (wave * 32 + l32) + 4 * hf;
   const int strip_lane = (strip_s0 & 3) * C::SLEN + (strip_s0 & ~3);
@@ -427,7 +429,6 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     int kind = (MODE == kBwdDKDV) ? classify_tile(g, y0, y0 + C::BN - 1, xw0, xw0 + 31)
                                   : classify_tile(g, xw0, xw0 + 31, y0, y0 + C::BN - 1);
     if (xw0 >= L) kind = kTileEmpty;
-    if (kind == kTileFull && !unit_alpha) kind = kTilePartial;           // general alpha: generic path
 
     // The next tile's global loads are issued piecewise between the score products: the compute unit's
     // memory pipeline takes a 16-byte-per-lane load every few tens of cycles, and a wave that issues
@@ -567,7 +568,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
         // what the strip is indexed by, so the scores are seeded like a full tile's and only the mask is applied
         // per element (no table gathers, whose wait would also wait for the tile being fetched).
         // (Query-stationary passes only: in the dK/dV pass it measured 2-4 % slower than the gathers.)
-        const bool seeded = MODE != kBwdDKDV && kind == kTilePartial && unit_alpha && bias_h && min(xw0 + 32, L) - 1 < g.n;
+        const bool seeded = MODE != kBwdDKDV && kind == kTilePartial && bias_h && min(xw0 + 32, L) - 1 < g.n;
         if ((kind == kTileFull || seeded) && bias_h) {
           // the distance of every pair that counts is >= 0: seed the accumulators with the bias strip
           const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
@@ -691,7 +692,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
                 const bool vis = (MODE == kBwdDKDV) ? visible(g, y, x, delta) : visible(g, x, y, delta);
                 float bv = 0.f;
                 if (bias_h) bv = bias_h[vis ? delta : 0];
-                mixed(u, r, fmaf(sc1[u][r], a.alpha, bv), vis);
+                mixed(u, r, sc1[u][r] + bv, vis);
               }
           }
         }
