@@ -179,8 +179,10 @@ int hstu_truncate_bwd(int32_t batch, int64_t total_tokens, const int32_t* seq_of
  * straight into the column blocks of one gradient buffer (no concatenation).
  *
  * The four projections run through hipBLASLt (plain library GEMMs); the first call on a device creates a
- * hipBLASLt handle and the matmul plans, which allocate inside that library; later calls with the same shapes
- * allocate nothing.  Not thread-safe.  HSTU_ERR_UNSUPPORTED if the library has no kernel for a shape.
+ * hipBLASLt handle, and the first call with a new shape makes the matmul plans: it runs the library's candidate
+ * kernels on `stream`, waits for them and keeps the fastest (so that call allocates inside the GEMM library,
+ * blocks the host and must not be captured into a graph); later calls with the same shapes allocate nothing and
+ * only enqueue.  Not thread-safe.  HSTU_ERR_UNSUPPORTED if the library has no kernel for a shape.
  * T = 0: the forward writes nothing, the backward zeroes the weight gradients.
  */
 typedef struct hstu_layer_params {

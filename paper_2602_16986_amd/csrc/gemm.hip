@@ -1,8 +1,8 @@
 // Plain bf16 GEMMs of the layer's two projections and their backward, through hipBLASLt (library GEMMs: the
 // contractions here are ordinary dense products with at most a residual added).  Row-major operands are handed to
 // the column-major library as their transposes: D^T = op(B)^T op(A)^T.
-// Host code only.  One hipBLASLt handle per device and a small cache of matmul plans, created on first use;
-// not thread-safe.
+// Host code only.  One hipBLASLt handle per device and a small cache of matmul plans, created on first use (making
+// a plan times the library's candidate kernels on the stream and waits for them); not thread-safe.
 #include <hipblaslt/hipblaslt.h>
 
 #include "hstu_kernels.h"
@@ -25,7 +25,10 @@ bool g_has_handle[64];
 
 #define LT(x) do { if ((x) != HIPBLAS_STATUS_SUCCESS) return -1; } while (0)
 
-int make_plan(Plan& pl, size_t ws_bytes) {
+constexpr int kCandidates = 16;   // heuristic answers timed when a plan is made
+constexpr int kTrialRuns = 3;
+
+int make_plan(Plan& pl, const void* A, const void* B, const void* C, void* D, void* ws, size_t ws_bytes, hipStream_t stream) {
   hipblasLtHandle_t h = g_handle[pl.device];
   // column-major problem m = N, n = M: first operand is B, second is A
   hipblasOperation_t ta, tb;
@@ -48,13 +51,40 @@ int make_plan(Plan& pl, size_t ws_bytes) {
   hipblasLtMatmulPreference_t pref;
   LT(hipblasLtMatmulPreferenceCreate(&pref));
   LT(hipblasLtMatmulPreferenceSetAttribute(pref, HIPBLASLT_MATMUL_PREF_MAX_WORKSPACE_BYTES, &ws_bytes, sizeof(ws_bytes)));
-  hipblasLtMatmulHeuristicResult_t res[1];
+  hipblasLtMatmulHeuristicResult_t res[kCandidates];
   int found = 0;
-  const hipblasStatus_t st = hipblasLtMatmulAlgoGetHeuristic(h, pl.desc, pl.la, pl.lb, pl.lc, pl.ld, pref, 1, res, &found);
+  const hipblasStatus_t st = hipblasLtMatmulAlgoGetHeuristic(h, pl.desc, pl.la, pl.lb, pl.lc, pl.ld, pref, kCandidates, res, &found);
   hipblasLtMatmulPreferenceDestroy(pref);
   if (st != HIPBLAS_STATUS_SUCCESS || found < 1) return -2;
-  pl.algo = res[0].algo;
-  pl.ws_needed = res[0].workspaceSize;
+  // The library's first answer is not always its fastest kernel for these shapes (the split-K weight-gradient products
+  // differ by up to 5x between candidates): run every candidate on the real operands and keep the fastest.  The
+  // product is written kTrialRuns + 1 times per candidate into D, which the caller is about to overwrite anyway.
+  int best = 0;
+  if (found > 1) {
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return -1;
+    const float alpha = 1.0f, beta = pl.residual ? 1.0f : 0.0f;
+    float best_ms = 0.f;
+    bool have = false;
+    for (int i = 0; i < found; ++i) {
+      if (res[i].workspaceSize > ws_bytes) continue;
+      bool ok = true;
+      for (int r = 0; r <= kTrialRuns && ok; ++r) {
+        if (r == 1) ok = hipEventRecord(e0, stream) == hipSuccess;
+        ok = ok && hipblasLtMatmul(h, pl.desc, &alpha, B, pl.la, A, pl.lb, &beta, pl.residual ? C : D, pl.lc, D, pl.ld, &res[i].algo, ws,
+                                   ws_bytes, stream) == HIPBLAS_STATUS_SUCCESS;
+      }
+      ok = ok && hipEventRecord(e1, stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+      float ms = 0.f;
+      if (!ok || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) continue;
+      if (!have || ms < best_ms) { have = true; best_ms = ms; best = i; }
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (!have) return -2;
+  }
+  pl.algo = res[best].algo;
+  pl.ws_needed = res[best].workspaceSize;
   return 0;
 }
 
@@ -91,7 +121,7 @@ int gemm_bf16(int op, int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
     Plan np = {};
     np.device = device; np.op = op; np.M = M; np.N = N; np.K = K; np.lda = lda; np.ldb = ldb; np.ldc = ldc; np.ldd = ldd;
     np.residual = residual; np.d_fp32 = d_fp32;
-    const int rc = make_plan(np, ws_bytes);
+    const int rc = make_plan(np, A, B, C, D, ws, ws_bytes, stream);
     if (rc != 0) return rc;
     g_plans[g_nplans] = np;
     pl = &g_plans[g_nplans++];

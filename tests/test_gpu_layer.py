@@ -112,3 +112,81 @@ def test_layer_rejects_fp32_and_small_workspace(hb):
     dl.problem.params.attn.dtype = hb.HSTU_FP32
     with pytest.raises(hb.HstuError):
         dl.fwd()
+
+
+# ----------------------------------------------------------------------------------------------
+# the benchmark's configuration (layer-C3: 8 sequences of 8k-16k tokens, H=4, d=128, E=512)
+# ----------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def layer_c3(hb):
+    from paper_2602_16986_amd.runner import DeviceLayer
+    c = wl.layer_case("layer-C3")
+    dl = DeviceLayer(c)
+    dl.fwd()
+    dl.bwd()
+    torch.cuda.synchronize()
+    return c, dl
+
+
+def test_layer_full_size_forward_sampled_rows(layer_c3):
+    """Output rows of the full-size layer that the oracle computes one by one: the projection is evaluated for every
+    token (the sampled queries need all keys and values), attention, gated norm and output projection on the sample."""
+    c, dl = layer_c3
+    HD = c.H * c.d
+    rng = np.random.default_rng(7)
+    rows = np.sort(np.concatenate([rng.choice(c.T, size=96, replace=False), c.offsets[:-1], c.offsets[1:] - 1]))
+    x, _, _ = lorc.layer_norm_fwd(c.z, c.norm_w, c.eps)
+    pre = x @ c.w1.astype(np.float64).T
+    act = pre * lorc.sigmoid(pre)
+    u, v, q, k = (act[:, i * HD:(i + 1) * HD] for i in range(4))
+    shp = (c.T, c.H, c.d)
+    from oracle import hstu_oracle as orc
+    a = orc.attn_fwd(q.reshape(shp), k.reshape(shp), v.reshape(shp), c.offsets, rows=rows, **attn_kw(c)).reshape(len(rows), HD)
+    y, _, _ = orc.gated_norm_fwd(a, u[rows], c.gated_norm_w, None, c.eps)
+    ref = y @ c.w2.astype(np.float64).T + c.z[rows].astype(np.float64)
+    idx = torch.from_numpy(rows).to(dl.device)
+    check("A rows", f64(dl.attn_saved[idx]), a)
+    check("U rows", f64(dl.u_saved[idx]), u[rows])
+    check("out rows", f64(dl.out[idx]), ref)
+
+
+def test_layer_full_size_backward_against_composition(hb, layer_c3):
+    """At full size the backward is checked against its own steps done separately: the standalone attention and
+    gated-norm entry points (each checked against the oracle at this size elsewhere) for those two steps, torch fp32
+    on the GPU for the norms, projections and SiLU.  Same inputs, independent arithmetic for everything the layer adds."""
+    c, dl = layer_c3
+    F = torch.nn.functional
+    HD, T = c.H * c.d, c.T
+    z32 = dl.z.float().requires_grad_(True)
+    nw = dl.norm_w.clone().requires_grad_(True)
+    w1 = dl.w1.float().requires_grad_(True)
+    xn = F.layer_norm(z32, (c.E,), weight=nw, eps=c.eps)
+    pre = xn @ w1.T
+    act = F.silu(pre)
+    act_bf = act.detach().to(torch.bfloat16)                          # what the kernels see: [T, 4 H d], U V Q K
+    y_ref = F.layer_norm(dl.attn_saved.float(), (HD,), weight=dl.gated_norm_w, eps=c.eps) * dl.u_saved.float()
+    dout32 = dl.dout.float()
+    d_w2_ref = dout32.T @ y_ref
+    dy = (dout32 @ dl.w2.float()).to(torch.bfloat16)
+    # gated norm backward and attention backward through their own entry points
+    dattn, du = torch.empty_like(dy), torch.empty_like(dy)
+    dgw = torch.empty(HD, dtype=torch.float32, device=dl.device)
+    ws_n = hb.new_workspace(hb.hstu_gated_norm_bwd_workspace_bytes(T, HD), dl.device)
+    hb.hstu_gated_norm_bwd(dy, dl.attn_saved, dl.u_saved, dl.gated_norm_w, None, c.eps, dattn, du, dgw, None, ws_n)
+    shp = (T, c.H, c.d)
+    qv, kv, vv = (act_bf[:, i * HD:(i + 1) * HD].view(shp) for i in (2, 3, 1))
+    dact = torch.empty_like(act_bf)
+    dact[:, :HD] = du
+    dqv, dkv, dvv = (dact[:, i * HD:(i + 1) * HD].view(shp) for i in (2, 3, 1))
+    prob = hb.AttnProblem(qv, kv, vv, dattn.view(shp), dl.offsets, max_seqlen=c.max_seqlen, local_window=c.K1,
+                          global_prefix=c.K2, alpha=c.alpha, inv_n=1.0 / c.N, rab_table=dl.table, rab_bounds=dl.bounds)
+    ws_a = hb.new_workspace(hb.hstu_attn_workspace_bytes(prob, True), dl.device)
+    hb.hstu_attn_bwd(prob, qv, kv, vv, dattn.view(shp), dqv, dkv, dvv, ws_a)
+    torch.cuda.synchronize()
+    act.backward(dact.float())                                        # SiLU', both projection gradients, the norm
+    dz_ref = z32.grad + dout32
+    check("d gated_norm_w", f64(dl.d_gated_norm_w), f64(dgw))
+    check("d W2", f64(dl.d_w2), f64(d_w2_ref))
+    check("d W1", f64(dl.d_w1), f64(w1.grad))
+    check("d norm_w", f64(dl.d_norm_w), f64(nw.grad))
+    check("dZ", f64(dl.dz), f64(dz_ref))
