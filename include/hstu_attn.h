@@ -208,6 +208,30 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
                    const float* mean, const float* rstd, const void* dout, void* dz, float* d_norm_w, float* d_w1,
                    float* d_gated_norm_w, float* d_w2, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * FP8 around the layer's two projections (paper Section 4.2.2, "Mixed-Precision Training and Inference", and the FP8
+ * benchmarks of its appendix).  Format: OCP FP8 E4M3 (largest finite value 448), one fp32 scale per row:
+ *   scale = amax / 448 (1 for a row of zeros),  code = nearest E4M3 value, ties to even, of  y * (448 / amax),
+ * both divisions and the multiplication in fp32.
+ *
+ * hstu_norm_quant_fp8: the scaling and quantisation fused behind the norm that precedes a projection (Eq. 1: u = NULL;
+ *   Eq. 4: u = the gate).  y = (LayerNorm_D(a) * gamma + beta) * u as hstu_gated_norm_fwd computes it, never written;
+ *   q: E4M3 codes [T, D] (8-byte aligned), q_scale: fp32 [T]; mean, rstd: fp32 [T] or NULL.
+ *   gamma = NULL: no normalisation, y = a (times u when given): plain row-wise quantisation, e.g. of a weight matrix
+ *   [N, K] with one scale per output feature (beta must be NULL then).  a, u: [T, D] contiguous of `dtype`.
+ *
+ * hstu_fp8_gemm_bias2d: the projection on quantised operands with a two-dimensional additive operand
+ *   (D = A B + C with C in R^{m x n}: the post-attention projection accumulated with the residual, Eq. 5):
+ *     d[m, n] = a_scale[m] * b_scale[n] * sum_k a_q[m, k] * b_q[n, k]  +  c[m, n]
+ *   a_q: codes [M, K]; b_q: codes [N, K] (weights stored [out, in]); c: bf16 [M, N] or NULL; d: bf16 [M, N]; products
+ *   exact, fp32 accumulation, one rounding to bf16.  K in {128, 256, 512, 1024}, N a multiple of 64 (else
+ *   HSTU_ERR_UNSUPPORTED); all pointers 16-byte aligned.  c may be d (in-place accumulation).
+ */
+int hstu_norm_quant_fp8(int64_t T, int32_t D, int32_t dtype, const void* a, const void* u, const float* gamma,
+                        const float* beta, float eps, void* q, float* q_scale, float* mean, float* rstd, void* stream);
+int hstu_fp8_gemm_bias2d(int64_t M, int32_t N, int32_t K, const void* a_q, const float* a_scale, const void* b_q,
+                         const float* b_scale, const void* c, void* d, void* stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* hstu_status_string(int status);
 
@@ -223,7 +247,8 @@ int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, i
  * written: names[i] (static strings: "attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "gated_norm_fwd",
  * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_fwd", "schedule_bwd" [both backward lists, one launch], "bias_expand", "dbias_zero", "dbias_reduce",
  * "truncate_offsets", "truncate_fwd", "truncate_bwd", and from the layer entry points "layer_norm_fwd",
- * "gemm_uvqk", "silu_fwd", "gemm_out", "gemm_dy", "gemm_dw2", "silu_bwd", "gemm_dxn", "gemm_dw1", "layer_norm_bwd";
+ * "gemm_uvqk", "silu_fwd", "gemm_out", "gemm_dy", "gemm_dw2", "silu_bwd", "gemm_dxn", "gemm_dw1", "layer_norm_bwd",
+ * and "norm_quant_fp8", "fp8_gemm_bias2d";
  * "attn_bwd_dkdv" includes the kernel that combines the partial sums of cut key blocks) and
  * ms[i] = elapsed milliseconds.  HOST arrays.  Not thread-safe; enable(1) creates the events once. */
 int hstu_profile_enable(int on);

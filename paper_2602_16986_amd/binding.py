@@ -85,6 +85,10 @@ def _load() -> ctypes.CDLL:
     lib.hstu_layer_fwd.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hstu_layer_bwd.restype = ctypes.c_int
     lib.hstu_layer_bwd.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.hstu_norm_quant_fp8.restype = ctypes.c_int
+    lib.hstu_norm_quant_fp8.argtypes = [i64, i32, i32, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
+    lib.hstu_fp8_gemm_bias2d.restype = ctypes.c_int
+    lib.hstu_fp8_gemm_bias2d.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.hstu_profile_enable.restype = ctypes.c_int
     lib.hstu_profile_enable.argtypes = [ctypes.c_int]
     lib.hstu_profile_read.restype = ctypes.c_int
@@ -97,7 +101,8 @@ EXPORTS = ["hstu_attn_workspace_bytes", "hstu_attn_fwd", "hstu_attn_bwd", "hstu_
            "hstu_gated_norm_bwd_workspace_bytes", "hstu_gated_norm_bwd", "hstu_status_string",
            "hstu_attn_schedule_stats", "hstu_profile_enable", "hstu_profile_read",
            "hstu_truncate_offsets", "hstu_truncate_fwd", "hstu_truncate_bwd",
-           "hstu_layer_workspace_bytes", "hstu_layer_fwd", "hstu_layer_bwd"]
+           "hstu_layer_workspace_bytes", "hstu_layer_fwd", "hstu_layer_bwd",
+           "hstu_norm_quant_fp8", "hstu_fp8_gemm_bias2d"]
 
 
 def status_string(status: int) -> str:
@@ -297,6 +302,28 @@ def hstu_layer_bwd(prob: LayerProblem, z, u_saved, attn_saved, mean, rstd, dout,
                              workspace.numel(), _stream(stream))
     if st != HSTU_OK:
         raise HstuError(st, "hstu_layer_bwd")
+
+
+def hstu_norm_quant_fp8(a, u, gamma, beta, eps, q, q_scale, mean=None, rstd=None, stream=None) -> None:
+    """q (uint8 [T, D]) and q_scale (fp32 [T]) of the (gated) norm of a; gamma None: plain row-wise quantisation."""
+    T = a.shape[0]
+    D = a.numel() // T if T else int(np.prod(a.shape[1:]))
+    st = _lib.hstu_norm_quant_fp8(T, D, _dtype_code(a), _ptr(a), _ptr(u), _ptr(gamma), _ptr(beta), float(eps), _ptr(q),
+                                  _ptr(q_scale), _ptr(mean), _ptr(rstd), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_norm_quant_fp8")
+
+
+def hstu_fp8_gemm_bias2d(a_q, a_scale, b_q, b_scale, c, d, stream=None) -> None:
+    """d [M, N] bf16 = a_scale[m] b_scale[n] (a_q [M, K] b_q [N, K]^T) + c [M, N] (bf16 or None); codes as uint8."""
+    M, K = a_q.shape
+    N = b_q.shape[0]
+    assert b_q.shape[1] == K and tuple(d.shape) == (M, N) and a_q.is_contiguous() and b_q.is_contiguous() and d.is_contiguous()
+    assert c is None or (tuple(c.shape) == (M, N) and c.is_contiguous())
+    st = _lib.hstu_fp8_gemm_bias2d(M, N, K, _ptr(a_q), _ptr(a_scale), _ptr(b_q), _ptr(b_scale), _ptr(c), _ptr(d),
+                                   _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_fp8_gemm_bias2d")
 
 
 def hstu_profile_enable(on: bool) -> None:

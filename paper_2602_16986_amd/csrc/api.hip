@@ -393,4 +393,36 @@ int hstu_truncate_bwd(int32_t batch, int64_t total_tokens, const int32_t* seq_of
   return HSTU_OK;
 }
 
+// ---- FP8 around the projections (Section 4.2.2) ------------------------------------------------------------------
+int hstu_norm_quant_fp8(int64_t T, int32_t D, int32_t dtype, const void* a, const void* u, const float* gamma,
+                        const float* beta, float eps, void* q, float* q_scale, float* mean, float* rstd, void* stream) {
+  const int st = validate_norm(T, D, dtype);
+  if (st != HSTU_OK) return st;
+  if (T == 0) return HSTU_OK;
+  if (!a || !q || !q_scale) return HSTU_ERR_NULL;
+  if (beta && !gamma) return HSTU_ERR_NULL;
+  if (misaligned(a) || (u && misaligned(u)) || (gamma && misaligned(gamma)) || (beta && misaligned(beta)) ||
+      ((uintptr_t)q & 7u))
+    return HSTU_ERR_SHAPE;
+  NormFwdArgs p = {};
+  p.T = T; p.D = D; p.dtype = dtype; p.a = a; p.sa = D; p.u = u; p.su = D; p.gamma = gamma; p.beta = beta; p.eps = eps;
+  p.y = nullptr; p.sy = D; p.mean = mean; p.rstd = rstd; p.stats_in = 0;
+  ProfScope ps("norm_quant_fp8", (hipStream_t)stream);
+  if (launch_norm_quant_fwd(p, q, D, q_scale, (hipStream_t)stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
+int hstu_fp8_gemm_bias2d(int64_t M, int32_t N, int32_t K, const void* a_q, const float* a_scale, const void* b_q,
+                         const float* b_scale, const void* c, void* d, void* stream) {
+  if (M < 0 || N < 1 || K < 1) return HSTU_ERR_SHAPE;
+  if (!fp8_gemm_supported(N, K)) return HSTU_ERR_UNSUPPORTED;
+  if (M == 0) return HSTU_OK;
+  if (!a_q || !a_scale || !b_q || !b_scale || !d) return HSTU_ERR_NULL;
+  if (misaligned(a_q) || misaligned(b_q) || misaligned(b_scale) || (c && misaligned(c)) || misaligned(d)) return HSTU_ERR_SHAPE;
+  if ((M + 127) / 128 > 0x7fffffff) return HSTU_ERR_SHAPE;
+  ProfScope ps("fp8_gemm_bias2d", (hipStream_t)stream);
+  if (launch_fp8_gemm_bias2d(M, N, K, a_q, a_scale, b_q, b_scale, c, d, (hipStream_t)stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
 }  // extern "C"

@@ -107,6 +107,78 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gated_norm_fwd_kernel(cons
   }
 }
 
+// Forward with row-wise FP8 output (paper Section 4.2.2: the scaling and quantisation that the FP8 projections need are
+// fused into the norm kernel that precedes them, Eq. 1 and Eq. 4, so that the normalised rows never make a round trip
+// through memory in 16 bits).  Per row: y as in the kernel above (or, without gamma, the input rows themselves, times the
+// gate if there is one: plain row-wise quantisation, used for the weights), amax = max |y|, scale = amax / 448,
+// code = E4M3(y * (448 / amax)), ties to even.  All of it in fp32, one division per row and one multiplication per element.
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+
+template <typename E, int NCH>
+__global__ __launch_bounds__(64 * kRowsPerBlock) void norm_quant_fwd_kernel(const NormFwdArgs p, unsigned char* __restrict__ q,
+                                                                            int64_t sq, float* __restrict__ qscale) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave;
+  const int D = p.D;
+  if (row >= p.T) return;
+  const E* arow = (const E*)p.a + row * p.sa;
+  const E* urow = p.u ? (const E*)p.u + row * p.su : nullptr;
+  float a[NCH][8];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int e0 = (lane + 64 * c) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[c][i] = 0.f;
+    if (e0 < D) load8(arow, e0, a[c]);
+  }
+  float mu = 0.f, rs = 1.f;
+  if (p.gamma) row_stats<NCH>(a, lane, D, p.eps, mu, rs);
+  float amax = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int e0 = (lane + 64 * c) * 8;
+    if (e0 < D) {
+      float uv[8], gv[8], bv[8];
+      if (urow) load8(urow, e0, uv);
+      if (p.gamma) load8(p.gamma, e0, gv);
+      if (p.beta) load8(p.beta, e0, bv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float y = a[c][i];
+        if (p.gamma) y = (y - mu) * rs * gv[i] + (p.beta ? bv[i] : 0.f);
+        if (urow) y *= uv[i];
+        a[c][i] = y;
+        amax = fmaxf(amax, fabsf(y));
+      }
+    }
+  }
+  amax = wave_max(amax);
+  const float safe = amax > 0.f ? amax : 448.0f;
+  const float scale = safe / 448.0f;
+  const float inv = 448.0f / safe;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int e0 = (lane + 64 * c) * 8;
+    if (e0 < D) {
+      int w0 = 0, w1 = 0;
+      w0 = __builtin_amdgcn_cvt_pk_fp8_f32(a[c][0] * inv, a[c][1] * inv, w0, false);
+      w0 = __builtin_amdgcn_cvt_pk_fp8_f32(a[c][2] * inv, a[c][3] * inv, w0, true);
+      w1 = __builtin_amdgcn_cvt_pk_fp8_f32(a[c][4] * inv, a[c][5] * inv, w1, false);
+      w1 = __builtin_amdgcn_cvt_pk_fp8_f32(a[c][6] * inv, a[c][7] * inv, w1, true);
+      *(int2*)(q + row * sq + e0) = make_int2(w0, w1);
+    }
+  }
+  if (lane == 0) {
+    qscale[row] = scale;
+    if (p.gamma && p.mean) p.mean[row] = mu;
+    if (p.gamma && p.rstd) p.rstd[row] = rs;
+  }
+}
+
 // Backward.  Per row: ahat = (a - mu) rstd, dn = dy u, dU = dy (ahat gamma + beta), dahat = dn gamma,
 // dA = rstd (dahat - mean(dahat) - ahat mean(dahat ahat)).  Column sums dgamma = sum dn ahat and
 // dbeta = sum dn are kept per lane over the rows a wave visits, combined across the workgroup's
@@ -254,6 +326,13 @@ static hipError_t bwd_one(const NormBwdArgs& p, float* partial, hipStream_t stre
   return hipGetLastError();
 }
 
+template <typename E, int NCH>
+static hipError_t quant_one(const NormFwdArgs& p, void* q, int64_t sq, float* qscale, hipStream_t stream) {
+  const unsigned grid = (unsigned)((p.T + kRowsPerBlock - 1) / kRowsPerBlock);
+  hipLaunchKernelGGL((norm_quant_fwd_kernel<E, NCH>), dim3(grid), dim3(64 * kRowsPerBlock), 0, stream, p, (unsigned char*)q, sq, qscale);
+  return hipGetLastError();
+}
+
 static int chunks_per_lane(int D) {
   const int chunks = (D / 8 + 63) / 64;
   int nch = 1;
@@ -281,6 +360,28 @@ hipError_t launch_norm_fwd(const NormFwdArgs& p, hipStream_t stream) {
     default: return FWD_CALL(float, 16);
   }
 #undef FWD_CALL
+}
+
+hipError_t launch_norm_quant_fwd(const NormFwdArgs& p, void* q, int64_t sq, float* qscale, hipStream_t stream) {
+  const int nch = chunks_per_lane(p.D);
+#define Q_CALL(E, N) quant_one<E, N>(p, q, sq, qscale, stream)
+  if (p.dtype == 0) {
+    switch (nch) {
+      case 1: return Q_CALL(__bf16, 1);
+      case 2: return Q_CALL(__bf16, 2);
+      case 4: return Q_CALL(__bf16, 4);
+      case 8: return Q_CALL(__bf16, 8);
+      default: return Q_CALL(__bf16, 16);
+    }
+  }
+  switch (nch) {
+    case 1: return Q_CALL(float, 1);
+    case 2: return Q_CALL(float, 2);
+    case 4: return Q_CALL(float, 4);
+    case 8: return Q_CALL(float, 8);
+    default: return Q_CALL(float, 16);
+  }
+#undef Q_CALL
 }
 
 hipError_t launch_norm_bwd(const NormBwdArgs& p, float* partial, hipStream_t stream) {

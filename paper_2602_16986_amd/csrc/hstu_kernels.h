@@ -102,6 +102,9 @@ struct NormBwdArgs {
   float* dgamma; float* dbeta;              // dbeta may be nullptr
 };
 hipError_t launch_norm_fwd(const NormFwdArgs& p, hipStream_t stream);
+// same rows as launch_norm_fwd (p.y unused; p.gamma == nullptr: no normalisation), written as E4M3 codes q [T, D] (row stride
+// sq bytes) with one fp32 scale per row
+hipError_t launch_norm_quant_fwd(const NormFwdArgs& p, void* q, int64_t sq, float* qscale, hipStream_t stream);
 hipError_t launch_norm_bwd(const NormBwdArgs& p, float* partial, hipStream_t stream);   // partial: gated_norm_bwd_blocks(T) x 2 x D floats
 int gated_norm_bwd_blocks(int64_t T);
 hipError_t launch_gated_norm_fwd(int64_t T, int D, int dtype, const void* attn, const void* u, const float* gamma,
@@ -122,6 +125,11 @@ hipError_t launch_silu_bwd(int64_t T, int C, const void* pre, void* dact, hipStr
 enum { kGemmNT = 0, kGemmNN = 1, kGemmTN = 2 };
 int gemm_bf16(int op, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, const void* C,
               int64_t ldc, void* D, int64_t ldd, bool d_fp32, void* ws, size_t ws_bytes, hipStream_t stream);
+
+// fp8_gemm.hip: D[M,N] (bf16) = a_scale[m] b_scale[n] (Aq[M,K] Bq[N,K]^T) + C[M,N] (bf16 or nullptr), E4M3 codes
+bool fp8_gemm_supported(int N, int K);
+hipError_t launch_fp8_gemm_bias2d(int64_t M, int N, int K, const void* A, const float* a_scale, const void* B, const float* b_scale,
+                                  const void* C, void* D, hipStream_t stream);
 
 // truncate.hip (strides and row sizes in bytes, multiples of 16)
 hipError_t launch_truncate_offsets(int B, int keep, const int32_t* offsets, const int32_t* num_targets, int32_t* out,

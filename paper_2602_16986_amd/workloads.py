@@ -329,3 +329,21 @@ def layer_case(name: str, seed: int = 0) -> LayerCase:
 
 
 LAYER_SMALL = ["layer-small-dense", "layer-small-sparse-targets", "layer-small-nobias"]
+
+
+# ----------------------------------------------------------------------------------------------
+# FP8 projection with a two-dimensional additive operand (Section 4.2.2 and the FP8 GEMM table of the appendix)
+# ----------------------------------------------------------------------------------------------
+FP8_GEMM_SHAPES = {                      # (m, k = n) of the paper's table: "1M" and "250K" token rows, widths 512 and 1K
+    "1M-512": (1 << 20, 512), "1M-1K": (1 << 20, 1024), "250K-512": (250_000, 512), "250K-1K": (250_000, 1024),
+}
+
+
+def fp8_gemm_inputs(M: int, N: int, K: int, seed: int = 0, with_c: bool = True):
+    """Unquantised operands of D = A B^T + C: activations a [M, K] like gated-norm outputs (N(0,1) with a per-row spread of
+    magnitudes), weights b [N, K] ~ N(0, 1/K), residual c [M, N] ~ N(0,1); bf16-representable fp32 arrays."""
+    rng = np.random.default_rng(3000 + seed)
+    a = rng.standard_normal((M, K), dtype=np.float32) * rng.uniform(0.2, 3.0, (M, 1)).astype(np.float32)
+    b = rng.standard_normal((N, K), dtype=np.float32) * np.float32(1.0 / np.sqrt(K))
+    c = rng.standard_normal((M, N), dtype=np.float32) if with_c else None
+    return round_to_bf16(a), round_to_bf16(b), None if c is None else round_to_bf16(c)
