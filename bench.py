@@ -27,7 +27,9 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 4.783e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 5.024e9 + 0.090e9,
                           ("C3-dense", "attn_bwd_dkdv"): 4.472e9 + 0.180e9,
                           # profiles/truncation_at_3072_512.md
-                          ("AT-3072-512", "truncate_fwd"): 0.1343e9 + 0.1342e9, ("AT-3072-512", "truncate_bwd"): 0.1343e9 + 0.5240e9}
+                          ("AT-3072-512", "truncate_fwd"): 0.1343e9 + 0.1342e9, ("AT-3072-512", "truncate_bwd"): 0.1343e9 + 0.5240e9,
+                          # profiles/fp8_gemm_1m_512.md
+                          ("1M-512", "fp8_gemm_bias2d"): 1.658e9 + 1.074e9}
 
 
 def parse():
@@ -42,10 +44,11 @@ def parse():
     ap.add_argument("--fwd-only", action="store_true", help="time the forward attention only (profiling aid)")
     ap.add_argument("--bias-grad", action="store_true",
                     help="also compute the gradient of the relative-bias table in the attention backward")
-    ap.add_argument("--op", default="attention", choices=["attention", "truncate", "layer"],
+    ap.add_argument("--op", default="attention", choices=["attention", "truncate", "layer", "fp8gemm"],
                     help="attention: the hot path (default).  truncate: the row selection of attention truncation "
                          "(Section 4.3) on the AT-3072-512 batch, forward + backward, in GB/s against the HBM roofline.  "
                          "layer: one whole HSTU layer with rematerialisation (hstu_layer_fwd + hstu_layer_bwd) on layer-C3")
+    ap.add_argument("--fp8-shape", default="1M-512", help="--op fp8gemm: 1M-512, 1M-1K, 250K-512, 250K-1K (the paper's table)")
     ap.add_argument("--layer-case", default="layer-C3", help="layer workload for --op layer (layer-C3, layer-mid, ...)")
     ap.add_argument("--fused-qkvu", action="store_true",
                     help="attention op: Q, K, V, U as column blocks of one [T, 4*H*d] buffer (row stride 4x) instead of four tensors")
@@ -164,6 +167,71 @@ def bench_truncate(args):
     print(json.dumps(out))
 
 
+# FP8 GEMM with fused 2-D bias on H100, TFLOP/s (the paper's appendix table, "Bias-Fused FP8"); same metric, other hardware
+PAPER_FP8_GEMM_TFLOPS = {"1M-512": 414.0, "1M-1K": 734.0, "250K-512": 414.0, "250K-1K": 721.0}
+
+
+def bench_fp8_gemm(args):
+    """D = A B^T + C on row-wise quantised E4M3 operands, C and D bf16 (hstu_fp8_gemm_bias2d), at the (m, k = n) shapes of
+    the paper's FP8 GEMM table.  FLOPs 2 m n k; algorithmic bytes m (k + 4 n) + n k (A once, C once, D once, weights once)."""
+    import torch
+    from paper_2602_16986_amd import binding as hb
+    from paper_2602_16986_amd import workloads
+    M, KN = workloads.FP8_GEMM_SHAPES[args.fp8_shape]
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev).manual_seed(0)
+    # device-side synthetic operands with the recipe of workloads.fp8_gemm_inputs (drawn on the GPU: 1M x 1K on the host takes minutes)
+    a = (torch.randn(M, KN, generator=g, device=dev) * (0.2 + 2.8 * torch.rand(M, 1, generator=g, device=dev))).to(torch.bfloat16)
+    b = (torch.randn(KN, KN, generator=g, device=dev) / KN ** 0.5).to(torch.bfloat16)
+    c = torch.randn(M, KN, generator=g, device=dev).to(torch.bfloat16)
+    qa = torch.empty((M, KN), dtype=torch.uint8, device=dev)
+    sa = torch.empty(M, dtype=torch.float32, device=dev)
+    qb = torch.empty((KN, KN), dtype=torch.uint8, device=dev)
+    sb = torch.empty(KN, dtype=torch.float32, device=dev)
+    hb.hstu_norm_quant_fp8(a, None, None, None, 0.0, qa, sa)
+    hb.hstu_norm_quant_fp8(b, None, None, None, 0.0, qb, sb)
+    d = torch.empty_like(c)
+    step = lambda: hb.hstu_fp8_gemm_bias2d(qa, sa, qb, sb, c, d)
+    quant = lambda: hb.hstu_norm_quant_fp8(a, None, None, None, 0.0, qa, sa)
+    if args.calibrate_copy:
+        calibrate_copy(torch, dev)
+    for _ in range(args.warmup):
+        step()
+    ms = time_loop(step, args.steps, torch)
+    ms_quant = time_loop(quant, args.steps, torch)
+    hb.hstu_profile_enable(True)
+    kt = []
+    for _ in range(args.steps):
+        step()
+        kt += [t for _, t in hb.hstu_profile_read()]
+    hb.hstu_profile_enable(False)
+    kms = float(np.mean(kt))
+    flops = 2.0 * M * KN * KN
+    algo_bytes = float(M) * (KN + 4 * KN) + KN * KN
+    achieved = algo_bytes / (kms * 1e-3) / 1e9
+    out = {"metric": "TFLOP/s, FP8 GEMM with fused 2-D bias D = A B + C (m, k = n)", "value": flops / (ms * 1e-3) / 1e12,
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": flops / (ms * 1e-3) / 1e12 / PAPER_FP8_GEMM_TFLOPS[args.fp8_shape], "dtype": "fp8-e4m3",
+           "data": "synthetic", "config": {"workload": f"fp8-gemm-{args.fp8_shape}", "m": M, "k": KN, "n": KN},
+           "paper_h100_tflops": PAPER_FP8_GEMM_TFLOPS[args.fp8_shape],
+           "roofline": {"kernel": "fp8_gemm_bias2d", "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": achieved / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((args.fp8_shape, "fp8_gemm_bias2d"))},
+           "kernel_ms": {"fp8_gemm_bias2d": kms, "rowwise_quant_of_A": ms_quant},
+           "mfma_frac_of_fp8_peak": flops / (kms * 1e-3) / 1e12 / 5000.0,
+           "quant_gbs": float(M) * KN * 3 / (ms_quant * 1e-3) / 1e9}
+    if not args.no_cpu_baseline:
+        from oracle import fp8 as orc
+        rows = min(M, 1 << 18)
+        qa_h, sa_h, qb_h, sb_h = qa[:rows].cpu().numpy(), sa[:rows].cpu().numpy(), qb.cpu().numpy(), sb.cpu().numpy()
+        c_h = c[:rows].float().cpu().numpy()
+        t0 = time.time()
+        orc.gemm_bias2d(qa_h, sa_h, qb_h, sb_h, c_h)
+        dt = time.time() - t0
+        out["cpu_baseline"] = {"value": 2.0 * rows * KN * KN / dt / 1e12, "unit": "TFLOP/s", "cores": os.cpu_count(), "kind": "oracle",
+                               "sample": f"the first {rows} rows: decode + fp64 matmul + scales + C, {dt:.2f} s"}
+    print(json.dumps(out))
+
+
 def bench_layer(args):
     """One whole layer, forward + backward with rematerialisation.  Useful FLOPs: attention 4 d + 10 d per unmasked
     pair and head, projections 2 M N K each forward and twice that backward (the rematerialised U/V/Q/K GEMM of the
@@ -223,6 +291,8 @@ def main():
         return bench_truncate(args)
     if args.op == "layer":
         return bench_layer(args)
+    if args.op == "fp8gemm":
+        return bench_fp8_gemm(args)
     import torch
     from paper_2602_16986_amd import binding as hb
     from paper_2602_16986_amd import flops, workloads

@@ -24,10 +24,11 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kBM = 128;            // rows of A per workgroup
-constexpr int kBN = 64;             // output features per chunk
-constexpr int kEpiPitch = kBN + 4;  // floats per row of the epilogue staging area: 16-byte writes of 32 lanes hit all banks
 
-template <int KS>                   // K = 64 * KS
+// K = 64 * KS; kBN output features per chunk (64: full 128-byte row segments of C and D).  At K = 1024 the resident rows
+// of A take 128 registers per lane and one workgroup runs per compute unit; 32-feature chunks at two workgroups per compute
+// unit spilled and measured 25 % slower.
+template <int KS, int kBN>
 __global__ __launch_bounds__(256, KS >= 16 ? 1 : 2) void fp8_gemm_bias2d_kernel(int64_t M, int N, const unsigned char* __restrict__ A,
                                                                   const float* __restrict__ a_scale,
                                                                   const unsigned char* __restrict__ B,
@@ -36,9 +37,16 @@ __global__ __launch_bounds__(256, KS >= 16 ? 1 : 2) void fp8_gemm_bias2d_kernel(
   constexpr int K = 64 * KS;
   constexpr int CPR = K / 16;                         // 16-byte pieces per weight row
   constexpr int SWZ = CPR >= 16 ? 15 : CPR - 1;       // pieces are XORed with the low bits of the row
+  constexpr int kEpiPitch = kBN + 4;                  // floats per row of the epilogue staging area: the 16-byte writes of 32 lanes hit all banks
+  constexpr int NT = kBN / 32;                        // 32-feature accumulator tiles per chunk
+  constexpr int BP = kBN * CPR / 256;                 // 16-byte weight pieces per thread and chunk
+  constexpr int LPR = kBN / 8;                        // lanes per row in the row-contiguous layout of C and D
+  constexpr int RPI = 64 / LPR;                       // rows per wave instruction there
+  constexpr int NI = 32 / RPI;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* bl = smem;                           // [kBN][K] weight chunk
   float* epi = (float*)(smem + kBN * K);              // [4 waves][32][kEpiPitch]
+  float* sbl = epi + 4 * 32 * kEpiPitch;              // [N] weight scales
   const int t = threadIdx.x, w = t >> 6, l = t & 63, r = l & 31, h = l >> 5;
   const int64_t m0 = (int64_t)blockIdx.x * kBM + 32 * w;
   const int64_t gm = m0 + r;                          // this lane's token row
@@ -58,34 +66,36 @@ __global__ __launch_bounds__(256, KS >= 16 ? 1 : 2) void fp8_gemm_bias2d_kernel(
   const float sa = row_ok ? a_scale[gm] : 0.f;
 
   // ---- staging of a weight chunk: piece p = t + 256 i is piece p % CPR of row p / CPR
-  u32x4 bpre[KS];
+  u32x4 bpre[BP];
   auto bload = [&](int n0) {
 #pragma unroll
-    for (int i = 0; i < KS; ++i) {
+    for (int i = 0; i < BP; ++i) {
       const int p = t + 256 * i;
       bpre[i] = *(const u32x4*)(B + (int64_t)(n0 + p / CPR) * K + 16 * (p % CPR));
     }
   };
   auto bstore = [&]() {
 #pragma unroll
-    for (int i = 0; i < KS; ++i) {
+    for (int i = 0; i < BP; ++i) {
       const int p = t + 256 * i, n = p / CPR, c = p % CPR;
       *(u32x4*)(bl + n * K + 16 * (c ^ (n & SWZ))) = bpre[i];
     }
   };
-  // C in the row-contiguous layout of the stores: 8 lanes cover the 64 features of a row, 8 rows per instruction
-  const int er = l >> 3, ec = l & 7;
-  u32x4 cpre[4];
+  // C in the row-contiguous layout of the stores: LPR lanes cover the chunk's features of a row, RPI rows per instruction
+  const int er = l / LPR, ec = l % LPR;
+  u32x4 cpre[NI];
   auto cload = [&](int n0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t row = m0 + 8 * i + er;
+    for (int i = 0; i < NI; ++i) {
+      const int64_t row = m0 + RPI * i + er;
       cpre[i] = (u32x4){0u, 0u, 0u, 0u};
       if (C && row < M) cpre[i] = *(const u32x4*)(C + row * N + n0 + 8 * ec);
     }
   };
 
+  for (int i = t; i < N; i += 256) sbl[i] = b_scale[i];   // visible after the first barrier of the chunk loop
   bload(0);
+  cload(0);
   float* my_epi = epi + w * 32 * kEpiPitch;
   const int swz = r & SWZ;
   for (int n0 = 0; n0 < N; n0 += kBN) {
@@ -93,22 +103,15 @@ __global__ __launch_bounds__(256, KS >= 16 ? 1 : 2) void fp8_gemm_bias2d_kernel(
     bstore();
     __syncthreads();
     if (n0 + kBN < N) bload(n0 + kBN);                // the next chunk travels while this one is multiplied
-    cload(n0);
-    f32x4 sb[2][4];                                   // weight scales of this lane's accumulator registers
+    f32x16 acc[NT];
 #pragma unroll
-    for (int jt = 0; jt < 2; ++jt)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) sb[jt][g] = *(const f32x4*)(b_scale + n0 + 32 * jt + 8 * g + 4 * h);
-
-    f32x16 acc[2];
-#pragma unroll
-    for (int jt = 0; jt < 2; ++jt)
+    for (int jt = 0; jt < NT; ++jt)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[jt][q] = 0.f;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
 #pragma unroll
-      for (int jt = 0; jt < 2; ++jt) {
+      for (int jt = 0; jt < NT; ++jt) {
         const unsigned char* brow = bl + (32 * jt + r) * K;
         const u32x4 lo = *(const u32x4*)(brow + 16 * ((4 * s + 2 * h) ^ swz));
         const u32x4 hi = *(const u32x4*)(brow + 16 * ((4 * s + 2 * h + 1) ^ swz));
@@ -120,19 +123,20 @@ __global__ __launch_bounds__(256, KS >= 16 ? 1 : 2) void fp8_gemm_bias2d_kernel(
 
     // ---- epilogue: scale, transpose through LDS (this wave's area only), add C, round once, store full row segments
 #pragma unroll
-    for (int jt = 0; jt < 2; ++jt)
+    for (int jt = 0; jt < NT; ++jt)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
+        const f32x4 sb = *(const f32x4*)(sbl + n0 + 32 * jt + 8 * g + 4 * h);   // weight scales of this register group
         f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[jt][4 * g + e] * sa * sb[jt][g][e];
+        for (int e = 0; e < 4; ++e) v[e] = acc[jt][4 * g + e] * sa * sb[e];
         *(f32x4*)(my_epi + r * kEpiPitch + 32 * jt + 8 * g + 4 * h) = v;
       }
     // (LDS operations of one wave complete in order: the reads below see the writes above without a barrier)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t row = m0 + 8 * i + er;
-      const float* src = my_epi + (8 * i + er) * kEpiPitch + 8 * ec;
+    for (int i = 0; i < NI; ++i) {
+      const int64_t row = m0 + RPI * i + er;
+      const float* src = my_epi + (RPI * i + er) * kEpiPitch + 8 * ec;
       const f32x4 x0 = *(const f32x4*)src, x1 = *(const f32x4*)(src + 4);
       float o[8];
 #pragma unroll
@@ -146,19 +150,21 @@ __global__ __launch_bounds__(256, KS >= 16 ? 1 : 2) void fp8_gemm_bias2d_kernel(
         *(u32x4*)(D + row * N + n0 + 8 * ec) =
             (u32x4){pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
     }
+    // C of the next chunk: a whole chunk period (barriers, products) ahead of its use, in the registers just consumed
+    if (n0 + kBN < N) cload(n0 + kBN);
   }
 }
 
-template <int KS>
+template <int KS, int kBN>
 hipError_t launch_one(int64_t M, int N, const void* A, const float* a_scale, const void* B, const float* b_scale, const void* C,
                       void* D, hipStream_t stream) {
-  auto kern = fp8_gemm_bias2d_kernel<KS>;
-  const size_t smem = (size_t)kBN * 64 * KS + (size_t)4 * 32 * kEpiPitch * sizeof(float);
+  auto kern = fp8_gemm_bias2d_kernel<KS, kBN>;
+  const size_t smem = (size_t)kBN * 64 * KS + (size_t)4 * 32 * (kBN + 4) * sizeof(float) + (size_t)N * sizeof(float);
   static bool attr_set[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (!attr_set[dev]) {
-    const hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    const hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set[dev] = true;
   }
@@ -170,15 +176,15 @@ hipError_t launch_one(int64_t M, int N, const void* A, const float* a_scale, con
 
 }  // namespace
 
-bool fp8_gemm_supported(int N, int K) { return (K == 128 || K == 256 || K == 512 || K == 1024) && N >= 64 && N % 64 == 0; }
+bool fp8_gemm_supported(int N, int K) { return (K == 128 || K == 256 || K == 512 || K == 1024) && N >= 64 && N % 64 == 0 && N <= 8192; }
 
 hipError_t launch_fp8_gemm_bias2d(int64_t M, int N, int K, const void* A, const float* a_scale, const void* B, const float* b_scale,
                                   const void* C, void* D, hipStream_t stream) {
   switch (K) {
-    case 128: return launch_one<2>(M, N, A, a_scale, B, b_scale, C, D, stream);
-    case 256: return launch_one<4>(M, N, A, a_scale, B, b_scale, C, D, stream);
-    case 512: return launch_one<8>(M, N, A, a_scale, B, b_scale, C, D, stream);
-    case 1024: return launch_one<16>(M, N, A, a_scale, B, b_scale, C, D, stream);
+    case 128: return launch_one<2, 64>(M, N, A, a_scale, B, b_scale, C, D, stream);
+    case 256: return launch_one<4, 64>(M, N, A, a_scale, B, b_scale, C, D, stream);
+    case 512: return launch_one<8, 64>(M, N, A, a_scale, B, b_scale, C, D, stream);
+    case 1024: return launch_one<16, 64>(M, N, A, a_scale, B, b_scale, C, D, stream);
     default: return hipErrorInvalidValue;
   }
 }
