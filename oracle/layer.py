@@ -80,3 +80,25 @@ def layer_bwd(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, dout, *, norm_eps=
     d_w1 = dpre.T @ s["x"]
     dz_norm, d_nw = layer_norm_bwd(dx, z, norm_w, norm_eps)
     return dict(dz=dz_norm + dout, d_norm_w=d_nw, d_w1=d_w1, d_gated_norm_w=d_gw, d_w2=d_w2)
+
+
+def layer_fwd_fp8(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, *, norm_eps=1e-5, gated_eps=1e-5, **attn):
+    """The forward with both projections on row-wise quantised E4M3 operands (paper Section 4.2.2): X and Y are quantised
+    per token row as they leave their norms, W1 and W2 per output feature, the products are taken on the decoded codes and
+    rescaled, the residual Z enters the second projection as its two-dimensional additive operand.  Everything else as
+    layer_fwd.  Returns (out, intermediates)."""
+    from . import fp8
+    z = np.asarray(z, dtype=np.float64)
+    T, HD = z.shape[0], H * d
+    x, mean, rstd = layer_norm_fwd(z, norm_w, norm_eps)
+    xq, xs = fp8.rowwise_quant(x.astype(np.float32))
+    w1q, w1s = fp8.rowwise_quant(np.asarray(w1, dtype=np.float32))
+    pre = fp8.gemm_bias2d(xq, xs, w1q, w1s, None)
+    act = pre * sigmoid(pre)
+    u, v, q, k = (act[:, i * HD:(i + 1) * HD] for i in range(4))
+    a = orc.attn_fwd(q.reshape(T, H, d), k.reshape(T, H, d), v.reshape(T, H, d), offsets, **attn).reshape(T, HD)
+    y, _, _ = orc.gated_norm_fwd(a, u, gated_norm_w, None, gated_eps)
+    yq, ys = fp8.rowwise_quant(y.astype(np.float32))
+    w2q, w2s = fp8.rowwise_quant(np.asarray(w2, dtype=np.float32))
+    out = fp8.gemm_bias2d(yq, ys, w2q, w2s, z)
+    return out, dict(mean=mean, rstd=rstd, pre=pre, u=u, a=a, y=y)

@@ -114,3 +114,37 @@ def test_empty_batch():
     kw = dict(norm_eps=c.eps, gated_eps=c.eps, **attn_kw(c))
     out, _ = lorc.layer_fwd(c.z, c.norm_w, c.w1, c.gated_norm_w, c.w2, c.offsets, c.H, c.d, **kw)
     assert out.shape == (0, 12)
+
+
+def torch_fp8_rows(t):
+    """Row-wise E4M3 fake quantisation with torch's own float8 conversion: dequantised rows (fp64)."""
+    t32 = t.to(torch.float32)
+    amax = t32.abs().amax(dim=1, keepdim=True)
+    safe = torch.where(amax > 0, amax, torch.full_like(amax, 448.0))
+    q = (t32 * (torch.tensor(448.0) / safe)).to(torch.float8_e4m3fn).to(torch.float64)
+    return q * (safe / torch.tensor(448.0)).to(torch.float64)
+
+
+@pytest.mark.parametrize("i", [0, 2])
+def test_fp8_forward_matches_torch_fake_quantisation(i):
+    """The FP8 forward against the same layer written with torch ops, the quantised operands produced by torch's
+    float8_e4m3fn conversion (dequantised, then an ordinary fp64 matmul)."""
+    c = tiny_layer(i, E=16, **CASES[i])
+    t64 = lambda a: torch.tensor(np.asarray(a, dtype=np.float64))
+    z, nw, w1, gw, w2 = t64(c.z), t64(c.norm_w), t64(c.w1), t64(c.gated_norm_w), t64(c.w2)
+    T, HD = z.shape[0], c.H * c.d
+    x = F.layer_norm(z, (c.E,), weight=nw, eps=c.eps)
+    act = F.silu(torch_fp8_rows(x) @ torch_fp8_rows(w1).T)
+    u, v, q, k = act.split(HD, dim=1)
+    shp = (T, c.H, c.d)
+    a = dense_attention_torch(_AttnView(c), q.reshape(shp), k.reshape(shp), v.reshape(shp)).reshape(T, HD)
+    y = F.layer_norm(a, (HD,), weight=gw, eps=c.eps) * u
+    ref = torch_fp8_rows(y) @ torch_fp8_rows(w2).T + z
+    out, _ = lorc.layer_fwd_fp8(c.z, c.norm_w, c.w1, c.gated_norm_w, c.w2, c.offsets, c.H, c.d, norm_eps=c.eps, gated_eps=c.eps,
+                                **attn_kw(c))
+    np.testing.assert_allclose(out, ref.numpy(), rtol=1e-9, atol=1e-10)
+    # and it stays within the format's error of the unquantised layer
+    exact, _ = lorc.layer_fwd(c.z, c.norm_w, c.w1, c.gated_norm_w, c.w2, c.offsets, c.H, c.d, norm_eps=c.eps, gated_eps=c.eps,
+                              **attn_kw(c))
+    assert np.abs(out - exact).max() < 0.15 * np.abs(exact - c.z).max()
+    assert np.abs(out - exact).max() > 0
