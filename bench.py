@@ -49,6 +49,7 @@ def parse():
                          "(Section 4.3) on the AT-3072-512 batch, forward + backward, in GB/s against the HBM roofline.  "
                          "layer: one whole HSTU layer with rematerialisation (hstu_layer_fwd + hstu_layer_bwd) on layer-C3")
     ap.add_argument("--fp8-shape", default="1M-512", help="--op fp8gemm: 1M-512, 1M-1K, 250K-512, 250K-1K (the paper's table)")
+    ap.add_argument("--fp8", action="store_true", help="--op layer: forward with both projections in FP8 (Section 4.2.2)")
     ap.add_argument("--layer-case", default="layer-C3", help="layer workload for --op layer (layer-C3, layer-mid, ...)")
     ap.add_argument("--fused-qkvu", action="store_true",
                     help="attention op: Q, K, V, U as column blocks of one [T, 4*H*d] buffer (row stride 4x) instead of four tensors")
@@ -241,7 +242,7 @@ def bench_layer(args):
     from paper_2602_16986_amd import flops, workloads
     from paper_2602_16986_amd.runner import DeviceLayer
     c = workloads.layer_case(args.layer_case)
-    dl = DeviceLayer(c)
+    dl = DeviceLayer(c, fp8=args.fp8)
     HD = c.H * c.d
     fl = flops.attention_flops(c)
     gemm_fwd = 2.0 * c.T * c.E * 4 * HD + 2.0 * c.T * HD * c.E
@@ -268,11 +269,16 @@ def bench_layer(args):
            "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
            "config": {"workload": c.name, "B": c.B, "T": c.T, "H": c.H, "d": c.d, "E": c.E, "K1": c.K1, "K2": c.K2,
-                      "unmasked_pairs": fl["pairs"]},
+                      "unmasked_pairs": fl["pairs"], "forward_projections": "fp8-e4m3" if args.fp8 else "bf16"},
            "frac_of_peak": useful / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
            "roofline": {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
            "entry_ms": parts, "kernel_ms": kern,
+           # the forward's two projection blocks, each with the norm in front of it (and the SiLU behind the first)
+           "pre_attention_ms": sum(v for k, v in kern.items() if k in ("fwd:layer_norm_fwd", "fwd:gemm_uvqk", "fwd:silu_fwd",
+                                                                       "fwd:layer_norm_quant", "fwd:fp8_gemm_uvqk")),
+           "post_attention_ms": sum(v for k, v in kern.items() if k in ("fwd:gated_norm_fwd", "fwd:gemm_out", "fwd:gated_norm_quant",
+                                                                        "fwd:fp8_gemm_out")),
            "attention_share_of_step": (kern["fwd:attn_fwd"] + kern["bwd:attn_bwd_dq"] + kern["bwd:attn_bwd_dkdv"]) / ms_step,
            # activations that live from the forward to the backward, with and without rematerialisation (Section 4.2.2):
            # kept: Z, U, A and two statistics per row; otherwise also X, V, Q, K, Y and the pre-activations

@@ -194,6 +194,15 @@ typedef struct hstu_layer_params {
   const void* w1;             /* DEVICE bf16 [4*H*d, E] */
   const float* gated_norm_w;  /* DEVICE fp32[H*d] */
   const void* w2;             /* DEVICE bf16 [E, H*d] */
+  /* Optional FP8 forward (Section 4.2.2: both projections of the forward in FP8, everything else bf16).  When all four
+   * are given, hstu_layer_fwd quantises X and Y row-wise inside the two norm kernels (as hstu_norm_quant_fp8) and runs
+   * the projections as hstu_fp8_gemm_bias2d on these weights (the residual Z as the two-dimensional additive operand of
+   * the second); E and H*d must then be in {128, 256, 512, 1024}.  hstu_layer_bwd does not read them: it rematerialises
+   * and differentiates in bf16 with w1, w2.  All four NULL: bf16 forward. */
+  const void* w1_q;           /* DEVICE E4M3 codes [4*H*d, E], row-wise quantised w1 (hstu_norm_quant_fp8 with gamma = NULL) */
+  const float* w1_scale;      /* DEVICE fp32 [4*H*d] */
+  const void* w2_q;           /* DEVICE E4M3 codes [E, H*d] */
+  const float* w2_scale;      /* DEVICE fp32 [E] */
 } hstu_layer_params;
 
 /* Bytes of device scratch (256-byte aligned) for hstu_layer_fwd (for_backward = 0) or hstu_layer_bwd; 0 for an

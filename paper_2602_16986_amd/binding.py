@@ -46,6 +46,7 @@ class HstuLayerParams(ctypes.Structure):
         ("attn", HstuAttnParams), ("embed_dim", ctypes.c_int32), ("norm_eps", ctypes.c_float),
         ("gated_norm_eps", ctypes.c_float), ("norm_w", ctypes.c_void_p), ("w1", ctypes.c_void_p),
         ("gated_norm_w", ctypes.c_void_p), ("w2", ctypes.c_void_p),
+        ("w1_q", ctypes.c_void_p), ("w1_scale", ctypes.c_void_p), ("w2_q", ctypes.c_void_p), ("w2_scale", ctypes.c_void_p),
     ]
 
 
@@ -257,12 +258,14 @@ class LayerProblem:
 
     def __init__(self, *, num_heads, head_dim, embed_dim, total_tokens, seq_offsets, max_seqlen, norm_w, w1, gated_norm_w,
                  w2, num_targets=None, local_window=-1, global_prefix=0, alpha=1.0, inv_n=1.0, rab_table=None,
-                 rab_bounds=None, d_rab_table=None, norm_eps=1e-5, gated_norm_eps=1e-5):
+                 rab_bounds=None, d_rab_table=None, norm_eps=1e-5, gated_norm_eps=1e-5, w1_q=None, w1_scale=None, w2_q=None,
+                 w2_scale=None):
         hd = num_heads * head_dim
         assert w1.dtype == torch.bfloat16 and w2.dtype == torch.bfloat16 and w1.is_contiguous() and w2.is_contiguous()
         assert tuple(w1.shape) == (4 * hd, embed_dim) and tuple(w2.shape) == (embed_dim, hd)
         assert norm_w.dtype == torch.float32 and gated_norm_w.dtype == torch.float32
-        self._keep = (seq_offsets, num_targets, rab_table, rab_bounds, d_rab_table, norm_w, w1, gated_norm_w, w2)
+        self._keep = (seq_offsets, num_targets, rab_table, rab_bounds, d_rab_table, norm_w, w1, gated_norm_w, w2, w1_q, w1_scale,
+                      w2_q, w2_scale)
         p = HstuLayerParams()
         a = p.attn
         a.batch = int(seq_offsets.shape[0]) - 1
@@ -278,6 +281,7 @@ class LayerProblem:
         a.d_rab_table = _ptr(d_rab_table)
         p.embed_dim, p.norm_eps, p.gated_norm_eps = int(embed_dim), float(norm_eps), float(gated_norm_eps)
         p.norm_w, p.w1, p.gated_norm_w, p.w2 = _ptr(norm_w), _ptr(w1), _ptr(gated_norm_w), _ptr(w2)
+        p.w1_q, p.w1_scale, p.w2_q, p.w2_scale = _ptr(w1_q), _ptr(w1_scale), _ptr(w2_q), _ptr(w2_scale)   # optional FP8 forward
         self.params = p
 
     def ref(self):

@@ -28,12 +28,14 @@ constexpr int kBM = 128;            // rows of A per workgroup
 // K = 64 * KS; kBN output features per chunk (64: full 128-byte row segments of C and D).  At K = 1024 the resident rows
 // of A take 128 registers per lane and one workgroup runs per compute unit; 32-feature chunks at two workgroups per compute
 // unit spilled and measured 25 % slower.
-template <int KS, int kBN>
+// SILU: the epilogue applies x sigmoid(x) before the rounding (the first projection of the layer, Eq. 2), and output
+// features [0, u_cols) go to u_out [M, u_cols] instead of D (the gate is kept apart from the rest of the projection).
+template <int KS, int kBN, bool SILU>
 __global__ __launch_bounds__(256, KS >= 16 ? 1 : 2) void fp8_gemm_bias2d_kernel(int64_t M, int N, const unsigned char* __restrict__ A,
                                                                   const float* __restrict__ a_scale,
                                                                   const unsigned char* __restrict__ B,
                                                                   const float* __restrict__ b_scale, const __bf16* __restrict__ C,
-                                                                  __bf16* __restrict__ D) {
+                                                                  __bf16* __restrict__ D, __bf16* __restrict__ u_out, int u_cols) {
   constexpr int K = 64 * KS;
   constexpr int CPR = K / 16;                         // 16-byte pieces per weight row
   constexpr int SWZ = CPR >= 16 ? 15 : CPR - 1;       // pieces are XORed with the low bits of the row
@@ -146,19 +148,24 @@ __global__ __launch_bounds__(256, KS >= 16 ? 1 : 2) void fp8_gemm_bias2d_kernel(
       }
       o[0] += x0[0]; o[1] += x0[1]; o[2] += x0[2]; o[3] += x0[3];
       o[4] += x1[0]; o[5] += x1[1]; o[6] += x1[2]; o[7] += x1[3];
+      if constexpr (SILU) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * o[e]));
+      }
+      __bf16* dst = D + row * N + n0 + 8 * ec;
+      if constexpr (SILU) { if (n0 < u_cols) dst = u_out + row * u_cols + n0 + 8 * ec; }    // a chunk never straddles the gate's block
       if (row < M)
-        *(u32x4*)(D + row * N + n0 + 8 * ec) =
-            (u32x4){pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
+        *(u32x4*)dst = (u32x4){pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
     }
     // C of the next chunk: a whole chunk period (barriers, products) ahead of its use, in the registers just consumed
     if (n0 + kBN < N) cload(n0 + kBN);
   }
 }
 
-template <int KS, int kBN>
+template <int KS, int kBN, bool SILU>
 hipError_t launch_one(int64_t M, int N, const void* A, const float* a_scale, const void* B, const float* b_scale, const void* C,
-                      void* D, hipStream_t stream) {
-  auto kern = fp8_gemm_bias2d_kernel<KS, kBN>;
+                      void* D, void* u_out, int u_cols, hipStream_t stream) {
+  auto kern = fp8_gemm_bias2d_kernel<KS, kBN, SILU>;
   const size_t smem = (size_t)kBN * 64 * KS + (size_t)4 * 32 * (kBN + 4) * sizeof(float) + (size_t)N * sizeof(float);
   static bool attr_set[64];
   int dev = 0;
@@ -170,7 +177,7 @@ hipError_t launch_one(int64_t M, int N, const void* A, const float* a_scale, con
   }
   const unsigned grid = (unsigned)((M + kBM - 1) / kBM);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, stream, M, N, (const unsigned char*)A, a_scale, (const unsigned char*)B,
-                     b_scale, (const __bf16*)C, (__bf16*)D);
+                     b_scale, (const __bf16*)C, (__bf16*)D, (__bf16*)u_out, u_cols);
   return hipGetLastError();
 }
 
@@ -181,10 +188,22 @@ bool fp8_gemm_supported(int N, int K) { return (K == 128 || K == 256 || K == 512
 hipError_t launch_fp8_gemm_bias2d(int64_t M, int N, int K, const void* A, const float* a_scale, const void* B, const float* b_scale,
                                   const void* C, void* D, hipStream_t stream) {
   switch (K) {
-    case 128: return launch_one<2, 64>(M, N, A, a_scale, B, b_scale, C, D, stream);
-    case 256: return launch_one<4, 64>(M, N, A, a_scale, B, b_scale, C, D, stream);
-    case 512: return launch_one<8, 64>(M, N, A, a_scale, B, b_scale, C, D, stream);
-    case 1024: return launch_one<16, 64>(M, N, A, a_scale, B, b_scale, C, D, stream);
+    case 128: return launch_one<2, 64, false>(M, N, A, a_scale, B, b_scale, C, D, nullptr, 0, stream);
+    case 256: return launch_one<4, 64, false>(M, N, A, a_scale, B, b_scale, C, D, nullptr, 0, stream);
+    case 512: return launch_one<8, 64, false>(M, N, A, a_scale, B, b_scale, C, D, nullptr, 0, stream);
+    case 1024: return launch_one<16, 64, false>(M, N, A, a_scale, B, b_scale, C, D, nullptr, 0, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_fp8_gemm_silu(int64_t M, int N, int K, const void* A, const float* a_scale, const void* B, const float* b_scale,
+                                void* D, void* u_out, int u_cols, hipStream_t stream) {
+  if (u_cols % 64 != 0 || (u_cols > 0 && !u_out)) return hipErrorInvalidValue;
+  switch (K) {
+    case 128: return launch_one<2, 64, true>(M, N, A, a_scale, B, b_scale, nullptr, D, u_out, u_cols, stream);
+    case 256: return launch_one<4, 64, true>(M, N, A, a_scale, B, b_scale, nullptr, D, u_out, u_cols, stream);
+    case 512: return launch_one<8, 64, true>(M, N, A, a_scale, B, b_scale, nullptr, D, u_out, u_cols, stream);
+    case 1024: return launch_one<16, 64, true>(M, N, A, a_scale, B, b_scale, nullptr, D, u_out, u_cols, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -130,6 +130,9 @@ int gemm_bf16(int op, int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
 bool fp8_gemm_supported(int N, int K);
 hipError_t launch_fp8_gemm_bias2d(int64_t M, int N, int K, const void* A, const float* a_scale, const void* B, const float* b_scale,
                                   const void* C, void* D, hipStream_t stream);
+// the same product followed by x sigmoid(x); output features [0, u_cols) go to u_out [M, u_cols] instead of D (u_cols a multiple of 64)
+hipError_t launch_fp8_gemm_silu(int64_t M, int N, int K, const void* A, const float* a_scale, const void* B, const float* b_scale,
+                                void* D, void* u_out, int u_cols, hipStream_t stream);
 
 // truncate.hip (strides and row sizes in bytes, multiples of 16)
 hipError_t launch_truncate_offsets(int B, int keep, const int32_t* offsets, const int32_t* num_targets, int32_t* out,

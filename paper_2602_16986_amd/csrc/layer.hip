@@ -16,7 +16,7 @@ constexpr size_t kGemmWorkspace = (size_t)64 << 20;     // scratch offered to th
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct LayerLayout {
-  size_t attn, gemm, norm_partial, xn, pre, act, y, dy, dattn, dact, dxn, total;
+  size_t attn, gemm, norm_partial, xn, pre, act, y, dy, dattn, dact, dxn, qscale, total;
   size_t attn_bytes;
 };
 
@@ -36,6 +36,10 @@ int validate_layer(const hstu_layer_params* p) {
   const int64_t hd = (int64_t)p->attn.num_heads * p->attn.head_dim;
   if (hd > 8192) return HSTU_ERR_UNSUPPORTED;
   if (p->attn.total_tokens < 0) return HSTU_ERR_SHAPE;
+  const int nq = (p->w1_q != nullptr) + (p->w1_scale != nullptr) + (p->w2_q != nullptr) + (p->w2_scale != nullptr);
+  if (nq != 0 && nq != 4) return HSTU_ERR_NULL;
+  if (nq == 4 && (!fp8_gemm_supported((int)(4 * hd), p->embed_dim) || !fp8_gemm_supported(p->embed_dim, (int)hd)))
+    return HSTU_ERR_UNSUPPORTED;
   return HSTU_OK;
 }
 
@@ -49,6 +53,7 @@ LayerLayout make_layer_layout(const hstu_layer_params* p, int for_backward) {
   l.xn = off; off += align_up(T * E * 2);
   l.act = off; off += align_up(T * 4 * HD * 2);
   l.y = off; off += align_up(T * HD * 2);
+  l.qscale = off; off += align_up(2 * T * sizeof(float));     // row scales of the FP8 forward (X, then Y)
   if (for_backward) {
     const size_t pe = hstu_gated_norm_bwd_workspace_bytes((int64_t)T, (int32_t)E);
     const size_t ph = hstu_gated_norm_bwd_workspace_bytes((int64_t)T, (int32_t)HD);
@@ -88,7 +93,7 @@ int hstu_layer_fwd(const hstu_layer_params* p, const void* z, void* out, void* u
   if (!z || !out || !u_saved || !attn_saved || !mean || !rstd || !p->norm_w || !p->w1 || !p->gated_norm_w || !p->w2)
     return HSTU_ERR_NULL;
   if (bad16(z) || bad16(out) || bad16(u_saved) || bad16(attn_saved) || bad16(p->w1) || bad16(p->w2) || bad16(p->norm_w) ||
-      bad16(p->gated_norm_w))
+      bad16(p->gated_norm_w) || bad16(p->w1_q) || bad16(p->w1_scale) || bad16(p->w2_q) || bad16(p->w2_scale))
     return HSTU_ERR_SHAPE;
   const LayerLayout l = make_layer_layout(p, 0);
   if (l.attn_bytes == 0) return HSTU_ERR_SHAPE;
@@ -97,25 +102,52 @@ int hstu_layer_fwd(const hstu_layer_params* p, const void* z, void* out, void* u
   __bf16* xn = (__bf16*)(ws + l.xn);
   __bf16* act = (__bf16*)(ws + l.act);
   __bf16* y = (__bf16*)(ws + l.y);
-  {  // Eq. 1: X = LayerNorm(Z) * norm_w; the statistics are kept for the backward
+  const bool fp8 = p->w1_q != nullptr;
+  float* xscale = (float*)(ws + l.qscale);
+  float* yscale = xscale + T;
+  if (fp8) {  // Eq. 1 with the row-wise quantisation fused in: X leaves the norm kernel as E4M3 codes (in the X buffer) and scales
+    ProfScope ps("layer_norm_quant", stream);
+    NormFwdArgs n = {};
+    n.T = T; n.D = (int32_t)E; n.dtype = HSTU_BF16; n.a = z; n.sa = E; n.u = nullptr; n.su = 0; n.gamma = p->norm_w; n.beta = nullptr;
+    n.eps = p->norm_eps; n.y = nullptr; n.sy = E; n.mean = mean; n.rstd = rstd; n.stats_in = 0;
+    if (launch_norm_quant_fwd(n, xn, E, xscale, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  } else {  // Eq. 1: X = LayerNorm(Z) * norm_w; the statistics are kept for the backward
     ProfScope ps("layer_norm_fwd", stream);
     NormFwdArgs n = {};
     n.T = T; n.D = (int32_t)E; n.dtype = HSTU_BF16; n.a = z; n.sa = E; n.u = nullptr; n.su = 0; n.gamma = p->norm_w; n.beta = nullptr;
     n.eps = p->norm_eps; n.y = xn; n.sy = E; n.mean = mean; n.rstd = rstd; n.stats_in = 0;
     if (launch_norm_fwd(n, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
-  {  // Eq. 2: [U V Q K] = SiLU(X W1^T)
+  if (fp8) {  // Eq. 2 on the quantised operands, SiLU in the GEMM's epilogue, the gate written straight to the saved tensor
+    ProfScope ps("fp8_gemm_uvqk", stream);
+    if (launch_fp8_gemm_silu(T, (int)(4 * HD), (int)E, xn, xscale, p->w1_q, p->w1_scale, act, u_saved, (int)HD, stream) != hipSuccess)
+      return HSTU_ERR_LAUNCH;
+  } else {  // Eq. 2: [U V Q K] = SiLU(X W1^T)
     ProfScope ps("gemm_uvqk", stream);
     st = gemm_status(gemm_bf16(kGemmNT, T, 4 * HD, E, xn, E, p->w1, E, nullptr, 0, act, 4 * HD, false, ws + l.gemm, kGemmWorkspace, stream));
     if (st != HSTU_OK) return st;
   }
-  {
+  if (!fp8) {
     ProfScope ps("silu_fwd", stream);
     if (launch_silu_fwd(T, (int)(4 * HD), act, act, u_saved, (int)HD, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   // Eq. 3: A = attention(Q, K, V) on column blocks of the projection buffer
   st = hstu_attn_fwd(&ap, act + 2 * HD, act + 3 * HD, act + HD, attn_saved, ws + l.attn, l.attn_bytes, stream_);
   if (st != HSTU_OK) return st;
+  if (fp8) {
+    {  // Eq. 4 before f2 with the quantisation fused in
+      ProfScope ps("gated_norm_quant", stream);
+      NormFwdArgs n = {};
+      n.T = T; n.D = (int32_t)HD; n.dtype = HSTU_BF16; n.a = attn_saved; n.sa = HD; n.u = u_saved; n.su = HD; n.gamma = p->gated_norm_w;
+      n.beta = nullptr; n.eps = p->gated_norm_eps; n.y = nullptr; n.sy = HD; n.mean = nullptr; n.rstd = nullptr; n.stats_in = 0;
+      if (launch_norm_quant_fwd(n, y, HD, yscale, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    }
+    {  // f2 and the residual (Eq. 5) in one FP8 GEMM: Z is its two-dimensional additive operand
+      ProfScope ps("fp8_gemm_out", stream);
+      if (launch_fp8_gemm_bias2d(T, (int)E, (int)HD, y, yscale, p->w2_q, p->w2_scale, z, out, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    }
+    return HSTU_OK;
+  }
   {  // Eq. 4 before f2: Y = LayerNorm(A) * gated_norm_w (.) U
     ProfScope ps("gated_norm_fwd", stream);
     if (launch_gated_norm_fwd(T, (int)HD, HSTU_BF16, attn_saved, u_saved, p->gated_norm_w, nullptr, p->gated_norm_eps, y, nullptr, nullptr,

@@ -96,7 +96,7 @@ class DeviceWorkload:
 class DeviceLayer:
     """Device-resident copy of a LayerCase (token rows, weights) plus the buffers of hstu_layer_fwd / hstu_layer_bwd."""
 
-    def __init__(self, c, device="cuda:0", bias_grad: bool = False):
+    def __init__(self, c, device="cuda:0", bias_grad: bool = False, fp8: bool = False):
         assert c.dtype == "bf16"
         self.c = c
         self.device = dev = torch.device(device)
@@ -121,11 +121,20 @@ class DeviceLayer:
         self.d_w1 = torch.empty(4 * HD, c.E, dtype=torch.float32, device=dev)
         self.d_gated_norm_w = torch.empty(HD, dtype=torch.float32, device=dev)
         self.d_w2 = torch.empty(c.E, HD, dtype=torch.float32, device=dev)
+        fp8_args = {}
+        if fp8:   # weights quantised once, row-wise (one scale per output feature), by the library's own quantiser
+            self.w1_q = torch.empty(self.w1.shape, dtype=torch.uint8, device=dev)
+            self.w1_scale = torch.empty(self.w1.shape[0], dtype=torch.float32, device=dev)
+            self.w2_q = torch.empty(self.w2.shape, dtype=torch.uint8, device=dev)
+            self.w2_scale = torch.empty(self.w2.shape[0], dtype=torch.float32, device=dev)
+            hb.hstu_norm_quant_fp8(self.w1, None, None, None, 0.0, self.w1_q, self.w1_scale)
+            hb.hstu_norm_quant_fp8(self.w2, None, None, None, 0.0, self.w2_q, self.w2_scale)
+            fp8_args = dict(w1_q=self.w1_q, w1_scale=self.w1_scale, w2_q=self.w2_q, w2_scale=self.w2_scale)
         self.problem = hb.LayerProblem(num_heads=c.H, head_dim=c.d, embed_dim=c.E, total_tokens=c.T, seq_offsets=self.offsets,
                                        max_seqlen=c.max_seqlen, norm_w=self.norm_w, w1=self.w1, gated_norm_w=self.gated_norm_w,
                                        w2=self.w2, num_targets=self.num_targets, local_window=c.K1, global_prefix=c.K2,
                                        alpha=c.alpha, inv_n=1.0 / c.N, rab_table=self.table, rab_bounds=self.bounds,
-                                       d_rab_table=self.dtable, norm_eps=c.eps, gated_norm_eps=c.eps)
+                                       d_rab_table=self.dtable, norm_eps=c.eps, gated_norm_eps=c.eps, **fp8_args)
         self.ws_fwd = hb.new_workspace(hb.hstu_layer_workspace_bytes(self.problem, False), dev)
         self.ws_bwd = hb.new_workspace(hb.hstu_layer_workspace_bytes(self.problem, True), dev)
 
