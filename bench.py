@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--fp8-shape", default="1M-512", help="--op fp8gemm: 1M-512, 1M-1K, 250K-512, 250K-1K (the paper's table)")
     ap.add_argument("--fp8", action="store_true", help="--op layer: forward with both projections in FP8 (Section 4.2.2)")
     ap.add_argument("--layer-case", default="layer-C3", help="layer workload for --op layer (layer-C3, layer-mid, ...)")
+    ap.add_argument("--query-tail", type=int, default=0,
+                    help="attention op, forward only: compute only the last N history rows (and the candidates) of every sequence")
     ap.add_argument("--fused-qkvu", action="store_true",
                     help="attention op: Q, K, V, U as column blocks of one [T, 4*H*d] buffer (row stride 4x) instead of four tensors")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -308,6 +310,13 @@ def main():
     fl = flops.attention_flops(w)
     dw = DeviceWorkload(w, bias_grad=args.bias_grad, fused_qkvu=args.fused_qkvu)
     do_bwd = w.backward and not args.fwd_only
+    if args.query_tail > 0:                                  # forward over the last rows only: count only their pairs
+        do_bwd = False
+        fl = flops.attention_flops(w, pairs_per_head=flops.visible_pairs_tail(w.lengths, w.num_targets, w.K1, w.K2, args.query_tail))
+        dw.problem = hb.AttnProblem(dw.q, dw.k, dw.v, dw.out, dw.offsets, max_seqlen=w.max_seqlen, seq_offsets_host=w.offsets,
+                                    num_targets=dw.num_targets, local_window=w.K1, global_prefix=w.K2, alpha=w.alpha,
+                                    inv_n=1.0 / w.N, rab_table=dw.table, rab_bounds=dw.bounds, query_tail=args.query_tail)
+        dw.ws_fwd = hb.new_workspace(hb.hstu_attn_workspace_bytes(dw.problem, False), dw.device)
 
     def step():
         if do_bwd:
@@ -355,7 +364,8 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "pass": ("fwd+bwd+epilogue" if do_bwd else "fwd") + ("+dbias" if args.bias_grad else ""), "B": w.B, "T": w.T, "H": w.H,
+        "config": {"workload": w.name, "pass": ("fwd+bwd+epilogue" if do_bwd else "fwd") + ("+dbias" if args.bias_grad else "") +
+                           (f", last {args.query_tail} rows" if args.query_tail > 0 else ""), "B": w.B, "T": w.T, "H": w.H,
                    "d": w.d, "K1": w.K1, "K2": w.K2, "min_len": int(w.lengths.min()), "max_len": int(w.lengths.max()),
                    "unmasked_pairs": fl["pairs"]},
         "frac_of_peak": value / peak,

@@ -90,6 +90,12 @@ typedef struct hstu_attn_params {
   float* d_rab_table;       /* hstu_attn_bwd only, optional: DEVICE fp32[H, num_buckets] receives the gradient of
                                rab_table (sum of dS over the visible pairs of each bucket), overwritten; NULL = not
                                wanted; ignored by hstu_attn_fwd; requires rab_table */
+  int32_t query_tail;       /* hstu_attn_fwd only; 0: every row.  > 0: only the last query_tail history rows and the candidate
+                               rows of every sequence are computed (against all the keys they see); the other rows of `out` are
+                               left untouched.  This is the shape of the last full-length layer in front of an attention
+                               truncation (Section 4.3: only the rows that survive are needed) and of serving few recent rows
+                               against a long history.  hstu_attn_bwd and the layer entry points return HSTU_ERR_UNSUPPORTED
+                               when it is set */
 } hstu_attn_params;
 
 /* Bytes of device scratch (256-byte aligned) that hstu_attn_fwd (for_backward = 0)

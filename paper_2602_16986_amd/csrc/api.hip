@@ -38,7 +38,9 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
     const int rows = !for_backward ? fwd_block_rows(p->dtype, p->head_dim)
                                    : (s == 0 ? dq_block_rows(p->dtype, p->head_dim) : dkv_block_rows(p->dtype, p->head_dim));
     l.max_items[s] = (int)max_items_for(p, rows);
-    if (for_backward && s == 1) {                      // the dK/dV list also holds the pieces of cut key blocks
+    // the dK/dV list also holds the pieces of cut key blocks; so does the forward list over a query tail (few query
+    // blocks against long histories: their key axis is cut)
+    if ((for_backward && s == 1) || (!for_backward && p->query_tail > 0)) {
       l.slot_cap = slot_cap_for(l.max_items[s]);
       l.max_items[s] += l.slot_cap;
     }
@@ -48,6 +50,11 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
   }
   l.bias = off;
   off += align_up((size_t)p->num_heads * ((size_t)p->max_seqlen + 1) * sizeof(float));
+  if (!for_backward && p->query_tail > 0) {
+    l.splits = off; off += align_up((size_t)(l.slot_cap / 2 + 1) * sizeof(SplitItem));
+    l.partial = off;
+    off += align_up((size_t)l.slot_cap * fwd_block_rows(p->dtype, p->head_dim) * p->head_dim * sizeof(float));
+  }
   if (for_backward) {
     l.splits = off; off += align_up((size_t)(l.slot_cap / 2 + 1) * sizeof(SplitItem));
     l.partial = off;
@@ -80,6 +87,7 @@ int validate(const hstu_attn_params* p) {
   if ((p->rab_table == nullptr) != (p->rab_bounds == nullptr)) return HSTU_ERR_NULL;
   if (p->rab_table && (p->num_buckets < 1 || p->num_buckets > 4096)) return HSTU_ERR_SHAPE;
   if (p->d_rab_table && !p->rab_table) return HSTU_ERR_NULL;
+  if (p->query_tail < 0) return HSTU_ERR_SHAPE;
   if ((int64_t)p->total_tokens * p->num_heads / 32 + (int64_t)p->batch * p->num_heads > 0x7FFFFF00) return HSTU_ERR_SHAPE;
   if (p->seq_offsets_host) {
     const int32_t* o = p->seq_offsets_host;
@@ -104,6 +112,7 @@ AttnArgs make_args(const hstu_attn_params* p, const void* q, const void* k, cons
   a.K1 = p->local_window < 0 ? -1 : p->local_window;
   a.K2 = p->global_prefix;
   a.alpha = p->alpha; a.inv_n = p->inv_n;
+  a.query_tail = p->query_tail > 0 ? p->query_tail : 0;
   return a;
 }
 
@@ -205,11 +214,16 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
   a.max_items = l.max_items[0];
   a.header = (const SchedHeader*)(ws + l.header[0]);
   a.items = (const WorkItem*)(ws + l.items[0]);
+  const bool tail = p->query_tail > 0;
+  if (tail) {
+    a.splits = (const SplitItem*)(ws + l.splits);
+    a.partial = (float*)(ws + l.partial);
+  }
   {
     ProfScope ps("schedule_fwd", stream);
     if (launch_schedule(a, fwd_block_rows(p->dtype, p->head_dim), fwd_tile_rows(p->dtype, p->head_dim), false,
                         (SchedHeader*)(ws + l.header[0]), (WorkItem*)(ws + l.items[0]), (int32_t*)(ws + l.seq_base[0]),
-                        stream) != hipSuccess)
+                        tail ? (SplitItem*)(ws + l.splits) : nullptr, tail ? l.slot_cap : 0, stream) != hipSuccess)
       return HSTU_ERR_LAUNCH;
   }
   {
@@ -217,8 +231,9 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
     if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   {
-    ProfScope ps("attn_fwd", stream);
+    ProfScope ps("attn_fwd", stream);                      // with a query tail: includes the kernel that combines the pieces
     if (launch_attn_fwd(a, p->dtype, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    if (tail && launch_fwd_combine(a, p->dtype, l.slot_cap / 2, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   return HSTU_OK;
 }
@@ -227,6 +242,7 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
                   void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream_) {
   const int st = validate(p);
   if (st != HSTU_OK) return st;
+  if (p->query_tail > 0) return HSTU_ERR_UNSUPPORTED;    // the query tail is a forward (inference) feature
   if (p->total_tokens == 0 || p->batch == 0) {           // no pairs: the only output that still exists is a zero table gradient
     if (p->d_rab_table &&
         launch_fill_zero(p->d_rab_table, (size_t)p->num_heads * p->num_buckets, (hipStream_t)stream_) != hipSuccess)

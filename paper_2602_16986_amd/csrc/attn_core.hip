@@ -165,6 +165,8 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   const int xw0 = x0 + wave * 32;
   const int x = xw0 + l32;
   const bool x_ok = x < L;
+  // forward with a query tail: rows before q0 are neither computed nor written
+  const int q0 = (MODE == kFwd && a.query_tail > 0) ? max(g.n - a.query_tail, 0) : 0;
 
   // ---- operand roles
   const E *R1, *R2 = nullptr, *Y1, *Y2;
@@ -428,7 +430,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     // visible (no mask arithmetic, bias from the strip), or mixed (generic per-element path).
     int kind = (MODE == kBwdDKDV) ? classify_tile(g, y0, y0 + C::BN - 1, xw0, xw0 + 31)
                                   : classify_tile(g, xw0, xw0 + 31, y0, y0 + C::BN - 1);
-    if (xw0 >= L) kind = kTileEmpty;
+    if (xw0 >= L || xw0 + 31 < q0) kind = kTileEmpty;
 
     // The next tile's global loads are issued piecewise between the score products: the compute unit's
     // memory pipeline takes a 16-byte-per-lane load every few tens of cycles, and a wave that issues
@@ -783,12 +785,12 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     if (ntiles > t_begin) dacc_flush((ntiles - 1 - t_begin) & 1, tr.at(ntiles - 1));
   }
   // ---- epilogue: scale once, convert, store.  Lane x holds features ob*32 + 8*(r/4) + 4*hf + r%4.
-  if constexpr (MODE == kBwdDKDV) {
+  if constexpr (MODE == kBwdDKDV || MODE == kFwd) {
     if (item.slot >= 0) {
-      // a piece of a cut key block: raw fp32 sums go to its slot [dK, dV][block row][D]; dkdv_combine_kernel finishes
-      float* dst = a.partial + (((int64_t)item.slot * 2) * C::BX + (wave * 32 + l32)) * D;
+      // a piece of a cut block: raw fp32 sums go to its slot [outputs][block row][D]; the combine kernel finishes
+      float* dst = a.partial + (((int64_t)item.slot * C::NOUT) * C::BX + (wave * 32 + l32)) * D;
 #pragma unroll
-      for (int o = 0; o < 2; ++o)
+      for (int o = 0; o < C::NOUT; ++o)
 #pragma unroll
         for (int ob = 0; ob < C::OB; ++ob)
 #pragma unroll
@@ -798,7 +800,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
       return;
     }
   }
-  if (!x_ok) return;
+  if (!x_ok || x < q0) return;
 #pragma unroll
   for (int o = 0; o < C::NOUT; ++o) {
     E* dst;
@@ -825,27 +827,34 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   }
 }
 
-// Adds the partial sums of one cut key block in piece order (fixed order: deterministic), applies the
-// output scale and writes dK and dV rows.  Grid: (possible cut blocks, 8); block (b, rb, h) rows split 8 ways.
-template <typename E, int D>
-__global__ __launch_bounds__(256) void dkdv_combine_kernel(const AttnArgs a, int block_rows) {
+// Adds the partial sums of one cut block in piece order (fixed order: deterministic), applies the output scale and
+// writes the rows: dK and dV of a key block (FWD = false) or the attention output of a query block whose key axis was
+// cut (FWD = true: the forward over a query tail, few rows against long histories).
+// Grid: (possible cut blocks, 8); block (b, rb, h) rows split 8 ways.
+template <typename E, int D, bool FWD>
+__global__ __launch_bounds__(256) void combine_kernel(const AttnArgs a, int block_rows) {
   const int si = blockIdx.x;
   if (si >= a.header->splits) return;
   const SplitItem it = a.splits[si];
   const int seq0 = a.offsets[it.b], L = a.offsets[it.b + 1] - seq0;
   const int xb = it.rb_h >> 8, h = it.rb_h & 255;
   constexpr int VPR = D / 4;                                           // float4 per row
+  constexpr int NOUT = FWD ? 1 : 2;
+  int q0 = 0;
+  if (FWD && a.query_tail > 0) q0 = max(L - (a.num_targets ? a.num_targets[it.b] : 0) - a.query_tail, 0);
   const int rows_here = block_rows / 8;
-  for (int i = threadIdx.x; i < 2 * rows_here * VPR; i += 256) {
+  for (int i = threadIdx.x; i < NOUT * rows_here * VPR; i += 256) {
     const int o = i / (rows_here * VPR), r = blockIdx.y * rows_here + (i / VPR) % rows_here, c4 = i % VPR;
     const int x = xb * block_rows + r;
-    if (x >= L) continue;
+    if (x >= L || x < q0) continue;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int pc = 0; pc < it.pieces; ++pc)
-      acc += *(const f32x4*)(a.partial + ((((int64_t)(it.first_slot + pc) * 2 + o) * block_rows + r) * D) + 4 * c4);
-    const float scale = o == 0 ? a.inv_n * a.alpha : a.inv_n * kLn2;
+      acc += *(const f32x4*)(a.partial + ((((int64_t)(it.first_slot + pc) * NOUT + o) * block_rows + r) * D) + 4 * c4);
+    const float scale = (!FWD && o == 0) ? a.inv_n * a.alpha : a.inv_n * kLn2;
     acc *= scale;
-    E* dst = (E*)(o == 0 ? a.dk : a.dv) + (int64_t)(seq0 + x) * (o == 0 ? a.sk : a.sv) + (int64_t)h * D + 4 * c4;
+    E* base = FWD ? (E*)a.out : (E*)(o == 0 ? a.dk : a.dv);
+    const int64_t stride = FWD ? a.so : (o == 0 ? a.sk : a.sv);
+    E* dst = base + (int64_t)(seq0 + x) * stride + (int64_t)h * D + 4 * c4;
     if constexpr (sizeof(E) == 2) *(u32x2*)dst = (u32x2){pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
     else *(f32x4*)dst = acc;
   }
@@ -947,26 +956,34 @@ hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream
   return dispatch<kBwdDKDV, kDkvWavesBf16, kDkvWavesFp32>(a, dtype, stream);
 }
 
-hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream) {
+template <bool FWD>
+static hipError_t launch_combine(const AttnArgs& a, int dtype, int rows, int max_splits, hipStream_t stream) {
   if (max_splits <= 0) return hipSuccess;
-  const int rows = dkv_block_rows(dtype, a.D);
   const dim3 grid(max_splits, 8), block(256);
   if (dtype == 0) {
     switch (a.D) {
-      case 32: hipLaunchKernelGGL((dkdv_combine_kernel<__bf16, 32>), grid, block, 0, stream, a, rows); break;
-      case 64: hipLaunchKernelGGL((dkdv_combine_kernel<__bf16, 64>), grid, block, 0, stream, a, rows); break;
-      case 128: hipLaunchKernelGGL((dkdv_combine_kernel<__bf16, 128>), grid, block, 0, stream, a, rows); break;
+      case 32: hipLaunchKernelGGL((combine_kernel<__bf16, 32, FWD>), grid, block, 0, stream, a, rows); break;
+      case 64: hipLaunchKernelGGL((combine_kernel<__bf16, 64, FWD>), grid, block, 0, stream, a, rows); break;
+      case 128: hipLaunchKernelGGL((combine_kernel<__bf16, 128, FWD>), grid, block, 0, stream, a, rows); break;
       default: return hipErrorInvalidValue;
     }
   } else {
     switch (a.D) {
-      case 32: hipLaunchKernelGGL((dkdv_combine_kernel<float, 32>), grid, block, 0, stream, a, rows); break;
-      case 64: hipLaunchKernelGGL((dkdv_combine_kernel<float, 64>), grid, block, 0, stream, a, rows); break;
-      case 128: hipLaunchKernelGGL((dkdv_combine_kernel<float, 128>), grid, block, 0, stream, a, rows); break;
+      case 32: hipLaunchKernelGGL((combine_kernel<float, 32, FWD>), grid, block, 0, stream, a, rows); break;
+      case 64: hipLaunchKernelGGL((combine_kernel<float, 64, FWD>), grid, block, 0, stream, a, rows); break;
+      case 128: hipLaunchKernelGGL((combine_kernel<float, 128, FWD>), grid, block, 0, stream, a, rows); break;
       default: return hipErrorInvalidValue;
     }
   }
   return hipGetLastError();
+}
+
+hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream) {
+  return launch_combine<false>(a, dtype, dkv_block_rows(dtype, a.D), max_splits, stream);
+}
+
+hipError_t launch_fwd_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream) {
+  return launch_combine<true>(a, dtype, fwd_block_rows(dtype, a.D), max_splits, stream);
 }
 
 }  // namespace hstu

@@ -44,14 +44,16 @@ struct AttnArgs {
   int32_t max_items;
   float* partial;                   // dK/dV pass: fp32 partial sums [slot][dK, dV][block row][D] of cut key blocks
   const SplitItem* splits;
+  int32_t query_tail;               // forward only, > 0: compute only the last query_tail history rows and the candidates of every sequence
   float* dbias_dist;                // dQ pass, optional: sum of dS per head and distance [H, bias_stride] (zeroed by the caller)
 };
 
 // schedule.hip
 // Builds the work list for blocks of `block_rows` rows (query rows in the forward and the dQ pass,
 // key rows when `key_major` is set) against column tiles of `tile_cols`.
+// `splits` / `slot_cap` (optional): blocks much longer than the rest may be cut into pieces that leave partial sums in slots.
 hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, bool key_major, SchedHeader* header,
-                           WorkItem* items, int32_t* seq_base, hipStream_t stream);
+                           WorkItem* items, int32_t* seq_base, SplitItem* splits, int slot_cap, hipStream_t stream);
 // The two lists of the backward pass in one launch: [0] query blocks (dQ pass), [1] key blocks (dK/dV pass).
 // `splits` / `slot_cap`: list of cut key blocks and number of partial-sum slots available to the dK/dV list.
 hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
@@ -76,6 +78,8 @@ hipError_t launch_dbias_reduce(const float* dist, const int32_t* bounds, int num
                                float* dtable, hipStream_t stream);
 // adds the partial sums of every cut key block in piece order, scales, converts and writes dK, dV
 hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream);
+// the same for query blocks of the forward whose key axis was cut (forward over a query tail): writes the output rows
+hipError_t launch_fwd_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream);
 
 // gated_norm.hip
 // Row-wise layer norm with weight (and optional bias), optionally gated by U; row strides in elements.

@@ -36,6 +36,7 @@ int validate_layer(const hstu_layer_params* p) {
   const int64_t hd = (int64_t)p->attn.num_heads * p->attn.head_dim;
   if (hd > 8192) return HSTU_ERR_UNSUPPORTED;
   if (p->attn.total_tokens < 0) return HSTU_ERR_SHAPE;
+  if (p->attn.query_tail != 0) return HSTU_ERR_UNSUPPORTED;     // every step of the layer runs on all rows
   const int nq = (p->w1_q != nullptr) + (p->w1_scale != nullptr) + (p->w2_q != nullptr) + (p->w2_scale != nullptr);
   if (nq != 0 && nq != 4) return HSTU_ERR_NULL;
   if (nq == 4 && (!fp8_gemm_supported((int)(4 * hd), p->embed_dim) || !fp8_gemm_supported(p->embed_dim, (int)hd)))

@@ -24,6 +24,7 @@ constexpr int kTargetChunks = 2048;  // ... and of about 1/2048 of all scheduled
 // One workgroup builds one list; the backward pass launches two (dQ blocks and dK/dV blocks) side by side.
 struct SchedJob {
   int block_rows, tile_cols, key_major;
+  int query_tail;                     // > 0 (query-major lists only): only the blocks that hold the last query_tail history rows or candidates
   int slot_cap;            // > 0: blocks much longer than the average may be cut along the streamed axis
   SchedHeader* header;
   WorkItem* items;
@@ -53,7 +54,9 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
                                                                  const int32_t* __restrict__ num_targets, int B, int H,
                                                                  int K1, int K2, SchedJob job0, SchedJob job1) {
   const SchedJob job = blockIdx.x == 0 ? job0 : job1;
-  const int block_rows = job.block_rows, tile_cols = job.tile_cols, key_major = job.key_major;
+  const int block_rows = job.block_rows, tile_cols = job.tile_cols, key_major = job.key_major, tail = job.query_tail;
+  // first block of a sequence that holds a query row to compute
+  auto first_block = [&](int L, int hist) { return tail > 0 ? max(hist - tail, 0) / block_rows : 0; };
   SchedHeader* header = job.header;
   WorkItem* items = job.items;
   int32_t* seq_base = job.seq_base;
@@ -75,7 +78,11 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   for (int c0 = 0; c0 < B; c0 += kSchedThreads) {
     const int b = c0 + tid;
     int nb = 0;
-    if (b < B) nb = (offsets[b + 1] - offsets[b] + block_rows - 1) / block_rows;
+    if (b < B) {
+      const int L = offsets[b + 1] - offsets[b];
+      nb = (L + block_rows - 1) / block_rows;
+      if (tail > 0 && nb > 0) nb -= first_block(L, L - (num_targets ? num_targets[b] : 0));
+    }
     scan[tid] = nb;
     __syncthreads();
     for (int off = 1; off < kSchedThreads; off <<= 1) {
@@ -119,10 +126,10 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     const int nb = (cached ? base_c[b + 1] : seq_base[b + 1]) - base_b;
     const int local = idx - base_b * H;
     h = local / nb;
-    rb = nb - 1 - (local % nb);
-    if (!want_cost) return;
     const int L = cached ? len_c[b] : offsets[b + 1] - offsets[b];
     SeqGeom g = {L, cached ? hist_c[b] : L - (num_targets ? num_targets[b] : 0), K1, K2};
+    rb = (L + block_rows - 1) / block_rows - 1 - (local % nb);          // last block first; with a query tail the leading blocks are absent
+    if (!want_cost) return;
     const int r0 = rb * block_rows, r1 = min(r0 + block_rows, L) - 1;
     const TileRanges tr = key_major ? row_tile_ranges(g, r0, r1, tile_cols) : tile_ranges(g, r0, r1, tile_cols);
     cost = tr.count();
@@ -274,8 +281,9 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
 }
 
 hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, bool key_major, SchedHeader* header,
-                           WorkItem* items, int32_t* seq_base, hipStream_t stream) {
-  const SchedJob job = {block_rows, tile_cols, key_major ? 1 : 0, 0, header, items, seq_base, nullptr};
+                           WorkItem* items, int32_t* seq_base, SplitItem* splits, int slot_cap, hipStream_t stream) {
+  const SchedJob job = {block_rows, tile_cols, key_major ? 1 : 0, key_major ? 0 : a.query_tail, splits ? slot_cap : 0, header, items,
+                        seq_base, splits};
   hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
                      a.K2, job, job);
   return hipGetLastError();
@@ -284,8 +292,8 @@ hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, boo
 hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
                                 WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* splits, int slot_cap,
                                 hipStream_t stream) {
-  const SchedJob j0 = {block_rows[0], tile_cols[0], 0, 0, header[0], items[0], seq_base[0], nullptr};
-  const SchedJob j1 = {block_rows[1], tile_cols[1], 1, slot_cap, header[1], items[1], seq_base[1], splits};
+  const SchedJob j0 = {block_rows[0], tile_cols[0], 0, 0, 0, header[0], items[0], seq_base[0], nullptr};
+  const SchedJob j1 = {block_rows[1], tile_cols[1], 1, 0, slot_cap, header[1], items[1], seq_base[1], splits};
   hipLaunchKernelGGL(schedule_kernel, dim3(2), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
                      a.K2, j0, j1);
   return hipGetLastError();

@@ -29,6 +29,17 @@ def visible_pairs(lengths, num_targets, K1: int, K2: int) -> int:
     return sum(visible_pairs_one(int(L), int(M), K1, K2) for L, M in zip(lengths, nt))
 
 
+def visible_pairs_tail(lengths, num_targets, K1: int, K2: int, tail: int) -> int:
+    """Pairs of the last min(n, tail) history rows and the candidates of every sequence: all pairs minus those of the
+    leading history rows (which see exactly what they would see in a sequence that ends with them)."""
+    nt = np.zeros(len(lengths), dtype=np.int64) if num_targets is None else num_targets
+    total = 0
+    for L, M in zip(lengths, nt):
+        n = int(L) - int(M)
+        total += visible_pairs_one(int(L), int(M), K1, K2) - visible_pairs_one(max(n - tail, 0), 0, K1, K2)
+    return total
+
+
 def attention_flops(w, pairs_per_head=None):
     p = visible_pairs(w.lengths, w.num_targets, w.K1, w.K2) if pairs_per_head is None else pairs_per_head
     pairs = p * w.H

@@ -130,3 +130,37 @@ def test_bias_table_gradient_at_c2_scale():
     scale = np.abs(ref).max()
     print(f"  dtable C2: max_abs_err={err:.3e} max|ref|={scale:.3e}", flush=True)
     assert err <= 2e-2 * max(1.0, scale) and err / scale <= 2e-2
+
+
+@pytest.mark.parametrize("name,tail", [("C3-dense", 512), ("C5", 1)])
+def test_full_size_query_tail(name, tail):
+    """The forward restricted to the last rows of every sequence at full size (the 16k -> 512 shape of an attention
+    truncation in front; candidates plus one history row on C5): sampled tail rows against the oracle, rows outside untouched."""
+    from paper_2602_16986_amd import binding as hb
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.config(name)
+    dw = DeviceWorkload(w)
+    prob = hb.AttnProblem(dw.q, dw.k, dw.v, dw.out, dw.offsets, max_seqlen=w.max_seqlen, seq_offsets_host=w.offsets,
+                          num_targets=dw.num_targets, local_window=w.K1, global_prefix=w.K2, alpha=w.alpha, inv_n=1.0 / w.N,
+                          rab_table=dw.table, rab_bounds=dw.bounds, query_tail=tail)
+    ws = hb.new_workspace(hb.hstu_attn_workspace_bytes(prob, False), dw.device)
+    dw.out.fill_(768.0)
+    hb.hstu_attn_fwd(prob, dw.q, dw.k, dw.v, dw.out, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    rows, outside = [], []
+    for b in range(w.B):
+        s0, s1 = int(w.offsets[b]), int(w.offsets[b + 1])
+        M = 0 if w.num_targets is None else int(w.num_targets[b])
+        q0 = s0 + max(s1 - s0 - M - tail, 0)
+        rows += [q0, s1 - 1] + rng.integers(q0, s1, size=6).tolist()
+        if q0 > s0:
+            outside += [s0, q0 - 1] + rng.integers(s0, q0, size=4).tolist()
+    rows = np.unique(np.array(rows, dtype=np.int64))
+    kw = dict(num_targets=w.num_targets, K1=w.K1, K2=w.K2, alpha=w.alpha, inv_n=1.0 / w.N, table=w.table, bounds=w.bounds)
+    q, k, v = (x.astype(np.float64) for x in (w.q, w.k, w.v))
+    got = dw.out.index_select(0, torch.from_numpy(rows).to(dw.device)).float().cpu().numpy().astype(np.float64)
+    print(f"query tail {tail} on {name}", flush=True)
+    check("A (tail rows)", got, orc.attn_fwd(q, k, v, w.offsets, rows=rows, **kw))
+    untouched = dw.out.index_select(0, torch.tensor(sorted(set(outside)), device=dw.device)).float()
+    assert torch.all(untouched == 768.0)

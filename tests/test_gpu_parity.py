@@ -230,3 +230,52 @@ def test_bias_table_gradient_general_alpha_and_targets(hb):
     w = wl.build("dbias-fp32", rng.integers(50, 300, size=3), 2, 64, "fp32", rng=rng, backward=True,
                  num_targets=np.array([3, 0, 9], dtype=np.int32))
     bias_gradient_case(w)
+
+
+# ----------------------------------------------------------------------------------------------
+# forward restricted to the last rows of every sequence (hstu_attn_params.query_tail)
+# ----------------------------------------------------------------------------------------------
+def tail_rows(w, tail):
+    """Global indices of the rows a query tail computes: the last min(n, tail) history rows and the candidates."""
+    rows = []
+    for b in range(w.B):
+        s0, s1 = int(w.offsets[b]), int(w.offsets[b + 1])
+        M = 0 if w.num_targets is None else int(w.num_targets[b])
+        n = s1 - s0 - M
+        rows.extend(range(s0 + max(n - tail, 0), s1))
+    return np.array(rows, dtype=np.int64)
+
+
+@pytest.mark.parametrize("name,tail", [("bf16-dense", 1), ("bf16-dense", 100), ("bf16-dense", 10000), ("bf16-sparse", 130),
+                                       ("bf16-targets", 64), ("bf16-targets-sparse", 7), ("bf16-d64", 33), ("fp32-sparse", 40)])
+def test_forward_query_tail(hb, name, tail):
+    """Only the tail rows are computed (against the oracle's rows, one by one) and every other output row keeps its old
+    contents; the scheduler visits fewer tiles than for the whole batch."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.small(name)
+    dw = DeviceWorkload(w)
+    dw.attn_fwd()
+    torch.cuda.synchronize()
+    all_tiles = hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)["tiles"]
+    prob = hb.AttnProblem(dw.q, dw.k, dw.v, dw.out, dw.offsets, max_seqlen=w.max_seqlen, seq_offsets_host=w.offsets,
+                          num_targets=dw.num_targets, local_window=w.K1, global_prefix=w.K2, alpha=w.alpha, inv_n=1.0 / w.N,
+                          rab_table=dw.table, rab_bounds=dw.bounds, query_tail=tail)
+    ws = hb.new_workspace(hb.hstu_attn_workspace_bytes(prob, False), dw.device)
+    sentinel = 12288.0
+    dw.out.fill_(sentinel)
+    hb.hstu_attn_fwd(prob, dw.q, dw.k, dw.v, dw.out, ws)
+    torch.cuda.synchronize()
+    rows = tail_rows(w, tail)
+    print(f"query tail {tail} on {name}: {len(rows)} of {w.T} rows", flush=True)
+    got = to_np(dw.out)
+    ref = orc.attn_fwd(w.q, w.k, w.v, w.offsets, rows=rows, **oracle_args(w))
+    check("A (tail rows)", got[rows], ref, TOL[w.dtype])
+    other = np.ones(w.T, dtype=bool)
+    other[rows] = False
+    assert np.all(got[other] == np.float64(torch.tensor(sentinel, dtype=dw.out.dtype).item())), "rows outside the tail were written"
+    tiles = hb.hstu_attn_schedule_stats(prob, ws, False)["tiles"]
+    assert tiles <= all_tiles
+    if len(rows) < w.T // 2:
+        assert tiles < all_tiles
+    with pytest.raises(hb.HstuError):                          # forward only
+        hb.hstu_attn_bwd(prob, dw.q, dw.k, dw.v, dw.dout, dw.dq, dw.dk, dw.dv, dw.ws_bwd)
