@@ -293,7 +293,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (sequences shard across GPUs "
-              "with no exchange in the attention path, see DESIGN.md)", file=sys.stderr)
+              "with no exchange in the attention path)", file=sys.stderr)
         sys.exit(2)
     if args.op == "truncate":
         return bench_truncate(args)
