@@ -43,16 +43,17 @@ def sigmoid(t):
     return 1.0 / (1.0 + np.exp(-t))
 
 
-def layer_fwd(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, *, norm_eps=1e-5, gated_eps=1e-5, **attn):
+def layer_fwd(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, *, norm_eps=1e-5, gated_eps=1e-5, pre_override=None, **attn):
     """Returns (out [T, E], intermediates dict).  ``attn``: keyword arguments of the attention oracle
-    (num_targets, K1, K2, alpha, inv_n, table, bounds)."""
+    (num_targets, K1, K2, alpha, inv_n, table, bounds).  ``pre_override``: pre-activations [T, 4 H d] to use in place of
+    X W1^T (the FP8 forward's, when the backward is to be taken at its activations)."""
     z = np.asarray(z, dtype=np.float64)
     w1, w2 = np.asarray(w1, dtype=np.float64), np.asarray(w2, dtype=np.float64)
     T = z.shape[0]
     HD = H * d
     assert w1.shape == (4 * HD, z.shape[1]) and w2.shape == (z.shape[1], HD)
     x, mean, rstd = layer_norm_fwd(z, norm_w, norm_eps)
-    pre = x @ w1.T                                   # [T, 4 H d]
+    pre = x @ w1.T if pre_override is None else np.asarray(pre_override, dtype=np.float64)      # [T, 4 H d]
     act = pre * sigmoid(pre)
     u, v, q, k = (act[:, i * HD:(i + 1) * HD] for i in range(4))
     a = orc.attn_fwd(q.reshape(T, H, d), k.reshape(T, H, d), v.reshape(T, H, d), offsets, **attn).reshape(T, HD)
@@ -61,13 +62,16 @@ def layer_fwd(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, *, norm_eps=1e-5, 
     return out, dict(x=x, mean=mean, rstd=rstd, pre=pre, u=u, v=v, q=q, k=k, a=a, y=y)
 
 
-def layer_bwd(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, dout, *, norm_eps=1e-5, gated_eps=1e-5, **attn):
-    """Returns dict(dz, d_norm_w, d_w1, d_gated_norm_w, d_w2) for upstream gradient dout [T, E]."""
+def layer_bwd(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, dout, *, norm_eps=1e-5, gated_eps=1e-5, pre_override=None, **attn):
+    """Returns dict(dz, d_norm_w, d_w1, d_gated_norm_w, d_w2) for upstream gradient dout [T, E].  With ``pre_override`` the
+    chain rule of the unquantised layer is evaluated at those pre-activations (backward of the FP8 forward with the
+    quantisation treated as the identity)."""
     dout = np.asarray(dout, dtype=np.float64)
     w1, w2 = np.asarray(w1, dtype=np.float64), np.asarray(w2, dtype=np.float64)
     T = dout.shape[0]
     HD = H * d
-    _, s = layer_fwd(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, norm_eps=norm_eps, gated_eps=gated_eps, **attn)
+    _, s = layer_fwd(z, norm_w, w1, gated_norm_w, w2, offsets, H, d, norm_eps=norm_eps, gated_eps=gated_eps,
+                     pre_override=pre_override, **attn)
     dy = dout @ w2                                   # out = Y W2^T + Z
     d_w2 = dout.T @ s["y"]
     da, du, d_gw, _ = orc.gated_norm_bwd(dy, s["a"], s["u"], gated_norm_w, None, gated_eps)

@@ -148,3 +148,26 @@ def test_fp8_forward_matches_torch_fake_quantisation(i):
                               **attn_kw(c))
     assert np.abs(out - exact).max() < 0.15 * np.abs(exact - c.z).max()
     assert np.abs(out - exact).max() > 0
+
+
+def test_backward_at_the_fp8_forward_activations():
+    """Backward of the FP8 forward with the quantisation treated as the identity: torch autograd through the unquantised
+    layer whose first projection is overridden in value (x W1^T + (pre_fp8 - x W1^T).detach()) gives the same gradients."""
+    c = tiny_layer(2, E=16, **CASES[2])
+    kw = dict(norm_eps=c.eps, gated_eps=c.eps, **attn_kw(c))
+    _, sf = lorc.layer_fwd_fp8(c.z, c.norm_w, c.w1, c.gated_norm_w, c.w2, c.offsets, c.H, c.d, **kw)
+    g = lorc.layer_bwd(c.z, c.norm_w, c.w1, c.gated_norm_w, c.w2, c.offsets, c.H, c.d, c.dout, pre_override=sf["pre"], **kw)
+    f64 = lambda a: torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
+    z, nw, w1, gw, w2 = f64(c.z), f64(c.norm_w), f64(c.w1), f64(c.gated_norm_w), f64(c.w2)
+    T, HD = z.shape[0], c.H * c.d
+    x = F.layer_norm(z, (c.E,), weight=nw, eps=c.eps)
+    plain = x @ w1.T
+    pre = plain + (torch.tensor(sf["pre"]) - plain).detach()
+    act = F.silu(pre)
+    u, v, q, k = act.split(HD, dim=1)
+    shp = (T, c.H, c.d)
+    a = dense_attention_torch(_AttnView(c), q.reshape(shp), k.reshape(shp), v.reshape(shp)).reshape(T, HD)
+    out = (F.layer_norm(a, (HD,), weight=gw, eps=c.eps) * u) @ w2.T + z
+    out.backward(torch.tensor(c.dout.astype(np.float64)))
+    for name, ref in (("dz", z.grad), ("d_norm_w", nw.grad), ("d_w1", w1.grad), ("d_gated_norm_w", gw.grad), ("d_w2", w2.grad)):
+        np.testing.assert_allclose(g[name], ref.numpy(), rtol=1e-9, atol=1e-10, err_msg=name)
