@@ -203,8 +203,9 @@ typedef struct hstu_layer_params {
   /* Optional FP8 forward (Section 4.2.2: both projections of the forward in FP8, everything else bf16).  When all four
    * are given, hstu_layer_fwd quantises X and Y row-wise inside the two norm kernels (as hstu_norm_quant_fp8) and runs
    * the projections as hstu_fp8_gemm_bias2d on these weights (the residual Z as the two-dimensional additive operand of
-   * the second); E and H*d must then be in {128, 256, 512, 1024}.  hstu_layer_bwd does not read them: it rematerialises
-   * and differentiates in bf16 with w1, w2.  All four NULL: bf16 forward. */
+   * the second); E and H*d must then be in {128, 256, 512, 1024}.  hstu_layer_bwd then rematerialises U, V, Q, K with the
+   * same FP8 projection (so that it differentiates at the forward's activations) and takes every gradient in bf16 with
+   * w1, w2 (straight-through: the quantisation is treated as the identity).  All four NULL: bf16 throughout. */
   const void* w1_q;           /* DEVICE E4M3 codes [4*H*d, E], row-wise quantised w1 (hstu_norm_quant_fp8 with gamma = NULL) */
   const float* w1_scale;      /* DEVICE fp32 [4*H*d] */
   const void* w2_q;           /* DEVICE E4M3 codes [E, H*d] */

@@ -184,7 +184,7 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
   if (!z || !u_saved || !attn_saved || !mean || !rstd || !dout || !dz || !p->norm_w || !p->w1 || !p->gated_norm_w || !p->w2)
     return HSTU_ERR_NULL;
   if (bad16(z) || bad16(u_saved) || bad16(attn_saved) || bad16(dout) || bad16(dz) || bad16(p->w1) || bad16(p->w2) ||
-      bad16(p->norm_w) || bad16(p->gated_norm_w))
+      bad16(p->norm_w) || bad16(p->gated_norm_w) || bad16(p->w1_q) || bad16(p->w1_scale))
     return HSTU_ERR_SHAPE;
   const LayerLayout l = make_layer_layout(p, 1);
   if (l.attn_bytes == 0) return HSTU_ERR_SHAPE;
@@ -206,14 +206,29 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
                               stream) != hipSuccess)
       return HSTU_ERR_LAUNCH;
   }
-  {  // rematerialise the normalised input from the saved statistics
+  const bool fp8 = p->w1_q != nullptr;
+  {  // rematerialise the normalised input from the saved statistics (in bf16: the weight gradient needs it in any case)
     ProfScope ps("layer_norm_fwd", stream);
     NormFwdArgs n = {};
     n.T = T; n.D = (int32_t)E; n.dtype = HSTU_BF16; n.a = z; n.sa = E; n.u = nullptr; n.su = 0; n.gamma = p->norm_w; n.beta = nullptr;
     n.eps = p->norm_eps; n.y = xn; n.sy = E; n.mean = const_cast<float*>(mean); n.rstd = const_cast<float*>(rstd); n.stats_in = 1;
     if (launch_norm_fwd(n, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
-  {  // rematerialise U, V, Q, K; the pre-activations stay for the SiLU backward
+  if (fp8) {
+    // the forward ran its first projection in FP8: rematerialise U, V, Q, K the same way, so that the backward differentiates
+    // at the activations the forward produced (codes and scales of X go to the dX buffer, which is free until the end)
+    float* xscale = (float*)(ws + l.qscale);
+    {
+      ProfScope ps("layer_norm_quant", stream);
+      NormFwdArgs n = {};
+      n.T = T; n.D = (int32_t)E; n.dtype = HSTU_BF16; n.a = z; n.sa = E; n.u = nullptr; n.su = 0; n.gamma = p->norm_w; n.beta = nullptr;
+      n.eps = p->norm_eps; n.y = nullptr; n.sy = E; n.mean = nullptr; n.rstd = nullptr; n.stats_in = 0;
+      if (launch_norm_quant_fwd(n, dxn, E, xscale, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    }
+    ProfScope ps("fp8_gemm_uvqk", stream);
+    if (launch_fp8_gemm_bias2d(T, (int)(4 * HD), (int)E, dxn, xscale, p->w1_q, p->w1_scale, nullptr, pre, stream) != hipSuccess)
+      return HSTU_ERR_LAUNCH;
+  } else {  // rematerialise U, V, Q, K; the pre-activations stay for the SiLU backward
     ProfScope ps("gemm_uvqk", stream);
     st = gemm_status(gemm_bf16(kGemmNT, T, 4 * HD, E, xn, E, p->w1, E, nullptr, 0, pre, 4 * HD, false, gws, kGemmWorkspace, stream));
     if (st != HSTU_OK) return st;
