@@ -138,6 +138,13 @@ hipError_t launch_fp8_gemm_bias2d(int64_t M, int N, int K, const void* A, const 
 hipError_t launch_fp8_gemm_silu(int64_t M, int N, int K, const void* A, const float* a_scale, const void* B, const float* b_scale,
                                 void* D, void* u_out, int u_cols, hipStream_t stream);
 
+// gemm_tn.hip: C[N1, N2] (fp32) = A[T, N1]^T B[T, N2] (bf16, row strides lda, ldb in elements), reduction cut into slabs
+// of token rows with fp32 partial tiles in `partial` (gemm_tn_workspace_bytes) added in a fixed order.  N1, N2 multiples of 128.
+bool gemm_tn_supported(int N1, int N2);
+size_t gemm_tn_workspace_bytes(int64_t T, int N1, int N2);
+hipError_t launch_gemm_tn(int64_t T, int N1, int N2, const void* A, int64_t lda, const void* B, int64_t ldb, float* C, float* partial,
+                          hipStream_t stream);
+
 // truncate.hip (strides and row sizes in bytes, multiples of 16)
 hipError_t launch_truncate_offsets(int B, int keep, const int32_t* offsets, const int32_t* num_targets, int32_t* out,
                                    hipStream_t stream);

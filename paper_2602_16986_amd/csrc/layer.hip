@@ -16,7 +16,7 @@ constexpr size_t kGemmWorkspace = (size_t)64 << 20;     // scratch offered to th
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct LayerLayout {
-  size_t attn, gemm, norm_partial, xn, pre, act, y, dy, dattn, dact, dxn, qscale, total;
+  size_t attn, gemm, norm_partial, xn, pre, act, y, dy, dattn, dact, dxn, qscale, tn_partial, total;
   size_t attn_bytes;
 };
 
@@ -64,6 +64,13 @@ LayerLayout make_layer_layout(const hstu_layer_params* p, int for_backward) {
     l.dattn = off; off += align_up(T * HD * 2);
     l.dact = off; off += align_up(T * 4 * HD * 2);
     l.dxn = off; off += align_up(T * E * 2);
+    size_t tn = 0;                                     // partial tiles of the two weight-gradient products
+    if (gemm_tn_supported((int)E, (int)HD)) tn = gemm_tn_workspace_bytes((int64_t)T, (int)E, (int)HD);
+    if (gemm_tn_supported((int)(4 * HD), (int)E)) {
+      const size_t t1 = gemm_tn_workspace_bytes((int64_t)T, (int)(4 * HD), (int)E);
+      tn = t1 > tn ? t1 : tn;
+    }
+    l.tn_partial = off; off += align_up(tn);
   }
   l.total = off;
   return l;
@@ -242,10 +249,14 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
     st = gemm_status(gemm_bf16(kGemmNN, T, HD, E, dout, E, p->w2, HD, nullptr, 0, dy, HD, false, gws, kGemmWorkspace, stream));
     if (st != HSTU_OK) return st;
   }
-  {
+  {  // weight gradients: this library's slab-split kernel when the widths are multiples of 128, else the GEMM library
     ProfScope ps("gemm_dw2", stream);
-    st = gemm_status(gemm_bf16(kGemmTN, E, HD, T, dout, E, y, HD, nullptr, 0, d_w2, HD, true, gws, kGemmWorkspace, stream));
-    if (st != HSTU_OK) return st;
+    if (gemm_tn_supported((int)E, (int)HD)) {
+      if (launch_gemm_tn(T, (int)E, (int)HD, dout, E, y, HD, d_w2, (float*)(ws + l.tn_partial), stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    } else {
+      st = gemm_status(gemm_bf16(kGemmTN, E, HD, T, dout, E, y, HD, nullptr, 0, d_w2, HD, true, gws, kGemmWorkspace, stream));
+      if (st != HSTU_OK) return st;
+    }
   }
   {  // gated norm backward: dA, dU (straight into the U block of the projection gradient), d gated_norm_w
     ProfScope ps("gated_norm_bwd", stream);
@@ -270,8 +281,13 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
   }
   {
     ProfScope ps("gemm_dw1", stream);
-    st = gemm_status(gemm_bf16(kGemmTN, 4 * HD, E, T, dact, 4 * HD, xn, E, nullptr, 0, d_w1, E, true, gws, kGemmWorkspace, stream));
-    if (st != HSTU_OK) return st;
+    if (gemm_tn_supported((int)(4 * HD), (int)E)) {
+      if (launch_gemm_tn(T, (int)(4 * HD), (int)E, dact, 4 * HD, xn, E, d_w1, (float*)(ws + l.tn_partial), stream) != hipSuccess)
+        return HSTU_ERR_LAUNCH;
+    } else {
+      st = gemm_status(gemm_bf16(kGemmTN, 4 * HD, E, T, dact, 4 * HD, xn, E, nullptr, 0, d_w1, E, true, gws, kGemmWorkspace, stream));
+      if (st != HSTU_OK) return st;
+    }
   }
   {  // input norm backward; the residual's gradient (dout) is added in the same pass
     ProfScope ps("layer_norm_bwd", stream);
