@@ -19,7 +19,8 @@ typedef __attribute__((address_space(3))) short4v* lds_s4;
 
 constexpr int kTile = 128;                 // output tile edge
 constexpr int kBK = 64;                    // token rows per LDS tile
-constexpr int kPitch = kTile * 2 + 16;     // bytes per LDS row (16 bytes of padding against bank conflicts)
+constexpr int kPitch = kTile * 2;          // bytes per LDS row; 16-byte chunk c of row r sits at chunk c ^ (4 (r % 4) + (r / 4) % 4): the
+                                           // rows that one transpose load touches fall into different bank groups
 constexpr int kOperand = kBK * kPitch;     // bytes of one operand tile
 
 __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const __bf16* __restrict__ A, int64_t lda, const __bf16* __restrict__ B,
@@ -28,8 +29,19 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const __bf16* __restric
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];              // [stage][A, B][row][pitch]
   const int t = threadIdx.x, w = t >> 6, l = t & 63, l32 = l & 31, hf = l >> 5, i16 = l & 15, grp16 = (l >> 4) & 1;
   const int tiles2 = N2 / kTile;
-  const int n1_0 = (blockIdx.x / tiles2) * kTile, n2_0 = (blockIdx.x % tiles2) * kTile;
-  const int64_t t_begin = (int64_t)blockIdx.y * slab_rows, t_end = min(t_begin + slab_rows, T);
+  // Workgroups go to the 8 dies round-robin in launch order; the tiles of one slab read the same rows of A and B, so they
+  // are renumbered to sit on one die (and its L2) together: die = id % 8 takes the ids' contiguous range [die * n/8, ...).
+  int tile_id = blockIdx.x, slab = blockIdx.y;
+  {
+    const int total = gridDim.x * gridDim.y, lin = blockIdx.y * gridDim.x + blockIdx.x;
+    if (total % 8 == 0) {
+      const int logical = (lin % 8) * (total / 8) + lin / 8;
+      tile_id = logical % gridDim.x;
+      slab = logical / gridDim.x;
+    }
+  }
+  const int n1_0 = (tile_id / tiles2) * kTile, n2_0 = (tile_id % tiles2) * kTile;
+  const int64_t t_begin = (int64_t)slab * slab_rows, t_end = min(t_begin + slab_rows, T);
   const int wi = w >> 1, wj = w & 1;       // this wave's 64 x 64 quarter of the tile
 
   // staging: thread -> rows t/16 + 16 i of the tile, 16-byte chunk t%16
@@ -52,19 +64,22 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const __bf16* __restric
     unsigned char* base = smem + stage * 2 * kOperand;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-      *(u32x4*)(base + (srow + 16 * i) * kPitch + 16 * schunk) = pa[i];
-      *(u32x4*)(base + kOperand + (srow + 16 * i) * kPitch + 16 * schunk) = pb[i];
+      const int off = (srow + 16 * i) * kPitch + 16 * (schunk ^ (4 * (srow & 3) + ((srow >> 2) & 3)));
+      *(u32x4*)(base + off) = pa[i];
+      *(u32x4*)(base + kOperand + off) = pb[i];
     }
   };
   // transposed fragment: rows [k0, k0 + 16) of an operand tile, features [f0, f0 + 32): lane l32 gets feature f0 + l32,
   // 8 values of k that depend on hf only.  Within a group of 16 lanes, lane i16 addresses row 4 hf + i16 / 4 (and +8),
   // chunk 2 (grp16) + (i16 % 4) / 2 of the 32 features, half 8 (i16 % 2) of that chunk.
   const int vchunk = 2 * grp16 + ((i16 & 3) >> 1), vbyte = 8 * (i16 & 1);
-  const int lane_off = (4 * hf + (i16 >> 2)) * kPitch + 16 * vchunk + vbyte;
+  // the rows' swizzle: row % 4 = i16 / 4, (row / 4) % 4 = hf for the first load and hf + 2 for the second (8 rows further)
+  const int lane_row = (4 * hf + (i16 >> 2)) * kPitch, lane_swz = 4 * (i16 >> 2);
+  const int vlo = 16 * (vchunk ^ hf) + vbyte, vhi = 16 * (vchunk ^ (hf + 2)) + vbyte + 8 * kPitch;
   auto trfrag = [&](const unsigned char* tile, int k0, int f0) -> bf16x8 {
-    const unsigned char* p = tile + k0 * kPitch + 2 * f0 + lane_off;
-    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)p);
-    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(p + 8 * kPitch));
+    const unsigned char* p = tile + k0 * kPitch + lane_row + 16 * ((f0 >> 3) ^ lane_swz);
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(p + vlo));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(p + vhi));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
 
@@ -100,7 +115,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const __bf16* __restric
   }
 
   // partial tile: accumulator lane = n2, registers = n1
-  float* out = partial + ((int64_t)blockIdx.y * N1 + n1_0 + 64 * wi) * N2 + n2_0 + 64 * wj + l32;
+  float* out = partial + ((int64_t)slab * N1 + n1_0 + 64 * wi) * N2 + n2_0 + 64 * wj + l32;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
