@@ -279,3 +279,29 @@ def test_forward_query_tail(hb, name, tail):
         assert tiles < all_tiles
     with pytest.raises(hb.HstuError):                          # forward only
         hb.hstu_attn_bwd(prob, dw.q, dw.k, dw.v, dw.dout, dw.dq, dw.dk, dw.dv, dw.ws_bwd)
+
+
+def test_schedule_is_a_longest_first_permutation(hb):
+    """The forward work list of a dense batch, read back from the workspace: every (sequence, row block, head) exactly once,
+    costs (tiles of the block: dense causal, no candidates -> last row / 32 + 1) in non-increasing order, equal costs in
+    natural order (sequence, head, block descending)."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    rng = np.random.default_rng(4)
+    for lengths in ([300, 0, 1, 129, 517, 64], rng.integers(1, 3000, size=23).tolist()):
+        w = wl.build("sched", lengths, 3, 128, "bf16", seed=1)
+        dw = DeviceWorkload(w)
+        dw.attn_fwd()
+        torch.cuda.synchronize()
+        st = hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)
+        n = st["items"]
+        items = dw.ws_fwd[256:256 + 24 * n].cpu().numpy().view(np.int32).reshape(n, 6)
+        BM = 128
+        want = {(b, rb, h) for b, L in enumerate(lengths) for rb in range((L + BM - 1) // BM) for h in range(w.H)}
+        got = [(int(b), int(rbh) >> 8, int(rbh) & 255) for b, rbh in items[:, :2]]
+        assert len(got) == len(want) and set(got) == want
+        cost = [(min((rb + 1) * BM, lengths[b]) - 1) // 32 + 1 for b, rb, h in got]
+        assert all(c0 >= c1 for c0, c1 in zip(cost, cost[1:])), "not longest-first"
+        for (a, ca), (b_, cb) in zip(zip(got, cost), zip(got[1:], cost[1:])):
+            if ca == cb:
+                assert (a[0], a[2], -a[1]) < (b_[0], b_[2], -b_[1]), "ties out of natural order"
+        assert np.all(items[:, 4] == -1)
