@@ -8,6 +8,9 @@
 // key-major list of the dK/dV pass a block far longer than the average (the key blocks of a
 // global prefix, which every query of the sequence sees) is cut into pieces along the query
 // axis; the pieces write partial sums that a small kernel adds up in a fixed order.
+// The cost of a block does not depend on the head, so pricing, cutting and sorting work on (sequence, block) pairs
+// and every entry of the sorted list is written once per head (heads adjacent): a single workgroup does all of this,
+// and its time grows with the number of keys it sorts.
 // Semi-local attention costs O((K1+K2) L) only because of the skipping (paper Section 4.2.1).
 #include "hstu_common.h"
 #include "hstu_kernels.h"
@@ -15,7 +18,7 @@
 namespace hstu {
 
 constexpr int kSchedThreads = 1024;
-constexpr int kSortMax = 8192;       // lists up to this size are sorted by cost in LDS
+constexpr int kSortMax = 8192;       // lists of up to this many (sequence, block) pairs are sorted by cost in LDS
 constexpr int kSeqCache = 1024;      // batches up to this size keep their block prefix sums and lengths in LDS
 constexpr int kItemsPerThread = kSortMax / kSchedThreads;
 constexpr int kMinChunk = 8;         // a long key block is cut into pieces of at least this many tiles ...
@@ -63,9 +66,8 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   __shared__ int32_t scan[kSchedThreads];
   __shared__ unsigned long long scan64[kSchedThreads];
   __shared__ uint32_t keys[kSortMax];                    // (inverted cost << 13) | entry
-  __shared__ uint32_t entry_item[kSortMax];              // entry -> item | (piece << 13)
-  __shared__ uint32_t cost_c[kSortMax];                  // item -> tiles
-  __shared__ uint16_t slot_c[kSortMax];                  // item -> first partial-sum slot, 0xFFFF = not cut
+  __shared__ uint32_t entry_item[kSortMax];              // entry -> pair | (piece << 13)
+  __shared__ uint16_t slot_c[kSortMax];                  // pair -> its first slot (x H: slot of head 0), 0xFFFF = not cut
   __shared__ int32_t base_c[kSeqCache + 1], len_c[kSeqCache], hist_c[kSeqCache];
   const bool cached = B <= kSeqCache;                    // else the searches below read seq_base / offsets from global memory
   __shared__ int32_t carry_s;
@@ -113,18 +115,20 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   __threadfence_block();
   __syncthreads();
   const int total = blocks_per_head * H;                 // <= max_items by construction of the bound
+  const int pairs = blocks_per_head;                     // (sequence, block) pairs: what is priced, cut and sorted
 
-  // natural order: sequence-major, then head, then block index descending.  Item idx -> (b, h, rb) and its tiles.
-  auto locate = [&](int idx, int& b, int& rb, int& h, int& cost, int& dense, bool want_cost) {
-    int lo = 0, hi = B;                                  // invariant: seq_base[lo]*H <= idx < seq_base[hi]*H
+  // natural order: sequence-major, then head, then block index descending.  Item idx of `heads` heads -> (b, h, rb) and
+  // its tiles; heads = 1 enumerates the pairs.
+  auto locate = [&](int idx, int heads, int& b, int& rb, int& h, int& cost, int& dense, bool want_cost) {
+    int lo = 0, hi = B;                                  // invariant: seq_base[lo]*heads <= idx < seq_base[hi]*heads
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
-      if ((long long)(cached ? base_c[mid] : seq_base[mid]) * H <= idx) lo = mid; else hi = mid;
+      if ((long long)(cached ? base_c[mid] : seq_base[mid]) * heads <= idx) lo = mid; else hi = mid;
     }
     b = lo;
     const int base_b = cached ? base_c[b] : seq_base[b];
     const int nb = (cached ? base_c[b + 1] : seq_base[b + 1]) - base_b;
-    const int local = idx - base_b * H;
+    const int local = idx - base_b * heads;
     h = local / nb;
     const int L = cached ? len_c[b] : offsets[b + 1] - offsets[b];
     SeqGeom g = {L, cached ? hist_c[b] : L - (num_targets ? num_targets[b] : 0), K1, K2};
@@ -136,9 +140,9 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     dense = (L + tile_cols - 1) / tile_cols;
   };
 
-  // 2. price the items.  Sorted lists: thread tid owns the items [tid * ipt, (tid + 1) * ipt).
-  const bool sorted = total <= kSortMax;
-  const int ipt = (total + kSchedThreads - 1) / kSchedThreads;
+  // 2. price the pairs.  Sorted lists: thread tid owns the pairs [tid * ipt, (tid + 1) * ipt).
+  const bool sorted = pairs <= kSortMax;
+  const int ipt = (pairs + kSchedThreads - 1) / kSchedThreads;
   unsigned long long my_tiles = 0, my_dense = 0;
   int my_cost[kItemsPerThread];
   if (sorted) {
@@ -146,19 +150,18 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     for (int k = 0; k < kItemsPerThread; ++k) {
       const int idx = tid * ipt + k;
       my_cost[k] = 0;
-      if (k < ipt && idx < total) {
+      if (k < ipt && idx < pairs) {
         int b, rb, h, cost, dense;
-        locate(idx, b, rb, h, cost, dense, true);
+        locate(idx, 1, b, rb, h, cost, dense, true);
         my_cost[k] = cost;
-        cost_c[idx] = (uint32_t)cost;
-        my_tiles += cost;
-        my_dense += dense;
+        my_tiles += (unsigned long long)cost * H;
+        my_dense += (unsigned long long)dense * H;
       }
     }
   } else {
     for (int idx = tid; idx < total; idx += kSchedThreads) {
       int b, rb, h, cost, dense;
-      locate(idx, b, rb, h, cost, dense, true);
+      locate(idx, H, b, rb, h, cost, dense, true);
       my_tiles += cost;
       my_dense += dense;
       items[idx] = WorkItem{b, (rb << 8) | h, 0, 0x7FFFFFFF, -1, 0};
@@ -179,18 +182,18 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     return;
   }
 
-  // 3. Cut items that are much longer than a workgroup slot's share into pieces of `chunk` tiles (key-major
+  // 3. Cut blocks that are much longer than a workgroup slot's share into pieces of `chunk` tiles (key-major
   // lists only: the few key blocks of a global prefix are seen by every query of their sequence).  Each piece
-  // becomes an entry of the list and accumulates into a partial-sum slot of its own.  The piece size doubles until
-  // the slots and the list fit.  Packed counters: entries | slots << 20 | cut items << 40.
+  // becomes an entry of the list and accumulates into a partial-sum slot of its own (one per head).  The piece size
+  // doubles until the slots and the list fit.  Packed counters, per pair: entries | slots << 20 | cut pairs << 40.
   int chunk = (int)min((unsigned long long)0x3FFFFFFF, max((unsigned long long)kMinChunk, (all_tiles + kTargetChunks - 1) / kTargetChunks));
-  unsigned long long excl = (unsigned long long)min(tid * ipt, total), sum = (unsigned long long)total;
+  unsigned long long excl = (unsigned long long)min(tid * ipt, pairs), sum = (unsigned long long)pairs;
   while (job.slot_cap > 0) {                               // no slots: one entry per item, in natural order
     unsigned long long mine = 0;
 #pragma unroll
     for (int k = 0; k < kItemsPerThread; ++k) {
       const int idx = tid * ipt + k;
-      if (k < ipt && idx < total) {
+      if (k < ipt && idx < pairs) {
         const int cost = my_cost[k];
         const bool cut = job.slot_cap > 0 && cost > 2 * chunk;
         const unsigned long long pieces = cut ? (unsigned long long)((cost + chunk - 1) / chunk) : 1ull;
@@ -199,31 +202,31 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     }
     excl = block_scan64(mine, scan64, sum);
     const int entries = (int)(sum & 0xFFFFF), slots = (int)((sum >> 20) & 0xFFFFF);
-    if (entries <= kSortMax && slots <= job.slot_cap) break;   // uniform: every thread sees the same totals
-    chunk *= 2;                                                // ends: with no item cut, entries = total <= kSortMax
+    if (entries <= kSortMax && (long long)slots * H <= job.slot_cap) break;   // uniform: every thread sees the same totals
+    chunk *= 2;                                                // ends: with no pair cut, entries = pairs <= kSortMax
   }
   const int entries = (int)(sum & 0xFFFFF), nsplit = (int)(sum >> 40);
-  if (tid == 0) *header = SchedHeader{entries, nsplit, (int64_t)all_tiles, (int64_t)dense_s, chunk, 0};
+  if (tid == 0) *header = SchedHeader{entries * H, nsplit * H, (int64_t)all_tiles, (int64_t)dense_s, chunk, 0};
   {
     int e = (int)(excl & 0xFFFFF), slot = (int)((excl >> 20) & 0xFFFFF), rank = (int)(excl >> 40);
 #pragma unroll
     for (int k = 0; k < kItemsPerThread; ++k) {
       const int idx = tid * ipt + k;
-      if (k < ipt && idx < total) {
+      if (k < ipt && idx < pairs) {
         const int cost = my_cost[k];
         const bool cut = job.slot_cap > 0 && cost > 2 * chunk;
         const int pieces = cut ? (cost + chunk - 1) / chunk : 1;
         slot_c[idx] = cut ? (uint16_t)slot : (uint16_t)0xFFFF;
         for (int c = 0; c < pieces; ++c) {
-          // ties keep the natural order: the heads of one (sequence, block) stay adjacent
+          // ties keep the natural order of the pairs (sequence-major, last block first)
           const uint32_t pc = (uint32_t)min(cut ? min(chunk, cost - c * chunk) : cost, 0x7FFFF);
           keys[e + c] = ((0x7FFFFu - pc) << 13) | (uint32_t)(e + c);      // entry < 8192 = 2^13
           entry_item[e + c] = (uint32_t)idx | ((uint32_t)c << 13);
         }
-        if (cut) {
+        if (cut) {                                       // the pieces of head h own the slots [(slot * H + h * pieces), + pieces)
           int b, rb, h, cost2, dense;
-          locate(idx, b, rb, h, cost2, dense, false);
-          job.splits[rank] = SplitItem{b, (rb << 8) | h, slot, pieces};
+          locate(idx, 1, b, rb, h, cost2, dense, false);
+          for (h = 0; h < H; ++h) job.splits[rank * H + h] = SplitItem{b, (rb << 8) | h, slot * H + h * pieces, pieces};
           slot += pieces;
           ++rank;
         }
@@ -269,14 +272,21 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     }
     if (j > 0) wave_stages(k, j);
   }
-  for (int pos = tid; pos < entries; pos += kSchedThreads) {
+  // 5. the list.  The attention kernels keep runs of kXcdGroup consecutive items on one die; a run is made of consecutive
+  // entries of one head (for equal costs these are neighbouring blocks of one sequence, which share most of the rows
+  // they stream), so a group of kXcdGroup sorted entries becomes H runs, one per head.
+  for (int e = tid; e < entries * H; e += kSchedThreads) {
+    const int grp = e / (kXcdGroup * H), within = e - grp * (kXcdGroup * H);
+    const int gsize = min(kXcdGroup, entries - grp * kXcdGroup);
+    const int hh = within / gsize, pos = grp * kXcdGroup + within - hh * gsize;
     const uint32_t ei = entry_item[keys[pos] & 0x1FFF];
     const int idx = (int)(ei & 0x1FFF), c = (int)(ei >> 13);
     const bool cut = slot_c[idx] != 0xFFFF;
     int b, rb, h, cost = 0, dense;
-    locate(idx, b, rb, h, cost, dense, cut);
-    items[pos] = cut ? WorkItem{b, (rb << 8) | h, c * chunk, min((c + 1) * chunk, cost), (int)slot_c[idx] + c, 0}
-                     : WorkItem{b, (rb << 8) | h, 0, 0x7FFFFFFF, -1, 0};
+    locate(idx, 1, b, rb, h, cost, dense, cut);
+    const int pieces = cut ? (cost + chunk - 1) / chunk : 1;
+    items[e] = cut ? WorkItem{b, (rb << 8) | hh, c * chunk, min((c + 1) * chunk, cost), (int)slot_c[idx] * H + hh * pieces + c, 0}
+                   : WorkItem{b, (rb << 8) | hh, 0, 0x7FFFFFFF, -1, 0};
   }
 }
 

@@ -282,11 +282,13 @@ def test_forward_query_tail(hb, name, tail):
 
 
 def test_schedule_is_a_longest_first_permutation(hb):
-    """The forward work list of a dense batch, read back from the workspace: every (sequence, row block, head) exactly once,
-    costs (tiles of the block: dense causal, no candidates -> last row / 32 + 1) in non-increasing order, equal costs in
-    natural order (sequence, head, block descending)."""
+    """The forward work list of a dense batch, read back from the workspace: every (sequence, row block, head) exactly once.
+    The list is made of groups of 4 (sequence, block) pairs, each group written once per head (4 consecutive items share a
+    head); the pairs come with non-increasing cost (tiles of the block: dense causal, no candidates -> last row / 32 + 1),
+    equal costs in natural order (sequence, block descending)."""
     from paper_2602_16986_amd.runner import DeviceWorkload
     rng = np.random.default_rng(4)
+    G = 4
     for lengths in ([300, 0, 1, 129, 517, 64], rng.integers(1, 3000, size=23).tolist()):
         w = wl.build("sched", lengths, 3, 128, "bf16", seed=1)
         dw = DeviceWorkload(w)
@@ -299,9 +301,16 @@ def test_schedule_is_a_longest_first_permutation(hb):
         want = {(b, rb, h) for b, L in enumerate(lengths) for rb in range((L + BM - 1) // BM) for h in range(w.H)}
         got = [(int(b), int(rbh) >> 8, int(rbh) & 255) for b, rbh in items[:, :2]]
         assert len(got) == len(want) and set(got) == want
-        cost = [(min((rb + 1) * BM, lengths[b]) - 1) // 32 + 1 for b, rb, h in got]
-        assert all(c0 >= c1 for c0, c1 in zip(cost, cost[1:])), "not longest-first"
-        for (a, ca), (b_, cb) in zip(zip(got, cost), zip(got[1:], cost[1:])):
-            if ca == cb:
-                assert (a[0], a[2], -a[1]) < (b_[0], b_[2], -b_[1]), "ties out of natural order"
+        assert n % w.H == 0
+        pairs = []
+        for g0 in range(0, n, G * w.H):
+            grp = got[g0:g0 + G * w.H]
+            size = len(grp) // w.H
+            first = [(b, rb) for b, rb, h in grp[:size]]
+            for h in range(w.H):
+                assert grp[h * size:(h + 1) * size] == [(b, rb, h) for b, rb in first]
+            pairs += first
+        cost = [(min((rb + 1) * BM, lengths[b]) - 1) // 32 + 1 for b, rb in pairs]
+        for (a, ca), (b_, cb) in zip(zip(pairs, cost), zip(pairs[1:], cost[1:])):
+            assert ca > cb or (ca == cb and (a[0], -a[1]) < (b_[0], -b_[1])), "not longest-first with natural ties"
         assert np.all(items[:, 4] == -1)
