@@ -41,6 +41,30 @@ def test_random_config(seed):
     run_case(draw_case(seed))
 
 
+def draw_many_heads(seed):
+    """More heads and longer sequences: the scheduler sorts (sequence, block) pairs and writes every entry once per head,
+    and key blocks of a global prefix are cut into pieces whose partial-sum slots are laid out per head."""
+    rng = np.random.default_rng(77_000 + seed)
+    B = int(rng.integers(1, 6))
+    L = rng.integers(0, int(rng.choice([200, 900, 1500, 2600])) + 1, size=B)
+    if L.sum() == 0:
+        L[0] = 33
+    H = int(rng.choice([1, 2, 4, 5, 8]))
+    d = int(rng.choice([32, 64, 128, 128]))
+    K1 = int(rng.choice([-1, 0, 1, 64, 129, 300, 700]))
+    K2 = int(rng.choice([0, 5, 64, 130, 257, 600])) if K1 >= 0 else 0
+    targets = None
+    if rng.random() < 0.4:
+        targets = np.array([int(rng.integers(0, min(l, 40) + 1)) for l in L], dtype=np.int32)
+    return wl.build(f"heads{seed}", L, H, d, "bf16", rng=rng, bias=bool(rng.random() < 0.8), K1=K1, K2=K2, num_targets=targets,
+                    backward=True)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_config_many_heads(seed):
+    run_case(draw_many_heads(seed))
+
+
 # ----------------------------------------------------------------------------------------------
 # the entry points around the attention: whole layer (bf16 and FP8 forward), FP8 GEMM, truncation, query tail
 # ----------------------------------------------------------------------------------------------
