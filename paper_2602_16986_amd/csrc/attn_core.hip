@@ -146,7 +146,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   // ---- schedule position -> work item.  Workgroups are dealt to the 8 dies round-robin by
-  // workgroup id; groups of kXcdGroup consecutive list entries are kept on one die.
+  // workgroup id; runs of kXcdGroup consecutive list entries (sorted blocks of one head) are kept on one die.
   const int wg = blockIdx.x;
   const int xcd = wg % kNumXcd, slot = wg / kNumXcd;
   const int pos = ((slot / kXcdGroup) * kNumXcd + xcd) * kXcdGroup + slot % kXcdGroup;

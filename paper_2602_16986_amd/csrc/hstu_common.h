@@ -19,7 +19,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;
 constexpr int kNumXcd = 8;          // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
-constexpr int kXcdGroup = 4;        // consecutive schedule entries kept on one die (the heads of one block of token rows)
+constexpr int kXcdGroup = 4;        // consecutive schedule entries kept on one die (the scheduler writes them as runs of one head)
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
