@@ -336,7 +336,7 @@ int hstu_gated_norm_fwd(int64_t T, int32_t D, int32_t dtype, const void* attn, c
 
 size_t hstu_gated_norm_bwd_workspace_bytes(int64_t T, int32_t D) {
   if (T < 0 || D < 1) return 0;
-  const size_t blocks = (size_t)gated_norm_bwd_blocks(T);
+  const size_t blocks = (size_t)gated_norm_bwd_blocks(T, D);
   return align_up((blocks > 0 ? blocks : 1) * 2 * (size_t)D * sizeof(float));
 }
 

@@ -276,6 +276,92 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(const No
   for (int i = threadIdx.x; i < 2 * D; i += blockDim.x) prow[i] = red[i];
 }
 
+// Backward for rows wider than 512 features: a workgroup of W waves shares one row, every thread owns one 16-byte chunk
+// of it (and the column sums of those 8 features over all the rows its workgroup visits, so the waves need no combination
+// at the end).  The row statistics cross the waves through LDS with two barriers per row: the sum of a first, then
+// sum (a - mu)^2, sum dahat and sum dahat (a - mu) together (mean(dahat ahat) = rstd times the last one / D).  The slots
+// alternate with the row parity, so a wave that runs ahead never overwrites what a slower one still reads.  One wave per
+// row needed 48 registers per 512 features (and spilled from 2048 features on).
+template <typename E, int W>
+__global__ __launch_bounds__(64 * W) void gated_norm_bwd_wide_kernel(const NormBwdArgs p, float* __restrict__ partial) {
+  __shared__ float red1[2][W];
+  __shared__ float red2[2][3][W];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int D = p.D, e0 = threadIdx.x * 8;
+  const bool on = e0 < D;
+  float gv[8], bv[8], gsum[8], bsum[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { gv[i] = 0.f; bv[i] = 0.f; gsum[i] = 0.f; bsum[i] = 0.f; }
+  if (on) {
+    load8(p.gamma, e0, gv);
+    if (p.beta) load8(p.beta, e0, bv);
+  }
+  const float inv_d = 1.0f / (float)D;
+  int par = 0;
+  for (int64_t row = blockIdx.x; row < p.T; row += gridDim.x, par ^= 1) {
+    const E* arow = (const E*)p.a + row * p.sa;
+    const E* dyrow = (const E*)p.dy + row * p.sdy;
+    const E* urow = p.u ? (const E*)p.u + row * p.su : nullptr;         // no gate: plain layer norm, no dU
+    const E* rrow = p.residual ? (const E*)p.residual + row * p.sres : nullptr;
+    float a[8], dn[8], dyv[8], rv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = 0.f; dn[i] = 0.f; dyv[i] = 0.f; rv[i] = 0.f; }
+    if (on) {
+      load8(arow, e0, a);
+      load8(dyrow, e0, dyv);
+      if (urow) load8(urow, e0, dn);
+      if (rrow) load8(rrow, e0, rv);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += a[i];
+    s = wave_sum(s);
+    if (lane == 0) red1[par][wave] = s;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < W; ++w) tot += red1[par][w];
+    const float mu = tot * inv_d;
+    float q = 0.f, s1 = 0.f, s2 = 0.f, dah[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float c = on ? a[i] - mu : 0.f;
+      dn[i] = urow ? dyv[i] * dn[i] : dyv[i];
+      dah[i] = dn[i] * gv[i];
+      q += c * c;
+      s1 += dah[i];
+      s2 += dah[i] * c;
+      a[i] = c;
+    }
+    q = wave_sum(q); s1 = wave_sum(s1); s2 = wave_sum(s2);
+    if (lane == 0) { red2[par][0][wave] = q; red2[par][1][wave] = s1; red2[par][2][wave] = s2; }
+    __syncthreads();
+    float tq = 0.f, t1 = 0.f, t2 = 0.f;
+#pragma unroll
+    for (int w = 0; w < W; ++w) { tq += red2[par][0][w]; t1 += red2[par][1][w]; t2 += red2[par][2][w]; }
+    const float rs = 1.0f / sqrtf(tq * inv_d + p.eps);
+    const float m1 = t1 * inv_d, m2 = rs * t2 * inv_d;
+    if (on) {
+      float duv[8], dav[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float ah = a[i] * rs;
+        duv[i] = dyv[i] * (ah * gv[i] + bv[i]);
+        gsum[i] += dn[i] * ah;
+        bsum[i] += dn[i];
+        dav[i] = rs * (dah[i] - m1 - ah * m2) + rv[i];     // rv: gradient that bypasses the norm (residual connection), else 0
+      }
+      if (urow) store8((E*)p.du + row * p.sdu, e0, duv);
+      store8((E*)p.da + row * p.sda, e0, dav);
+    }
+  }
+  if (on) {
+    float* prow = partial + (int64_t)blockIdx.x * 2 * D;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { prow[e0 + i] = gsum[i]; prow[D + e0 + i] = bsum[i]; }
+  }
+}
+
 // dgamma[c] = sum over workgroups of partial[blk][0][c]; dbeta likewise from partial[blk][1][c].
 // 64 columns x 16 row groups per workgroup; the 16 partial sums of a column are combined in a fixed order.
 __global__ __launch_bounds__(1024) void gated_norm_colsum_kernel(int nblk, int D, const float* __restrict__ partial,
@@ -297,9 +383,22 @@ __global__ __launch_bounds__(1024) void gated_norm_colsum_kernel(int nblk, int D
   }
 }
 
-int gated_norm_bwd_blocks(int64_t T) {
-  const int64_t need = (T + kBwdWaves - 1) / kBwdWaves;
-  return (int)(need < kMaxBwdBlocks ? need : kMaxBwdBlocks);
+// waves that share a row in the backward: 1 up to 512 features, else the power of two that gives every thread one chunk
+static int bwd_row_waves(int D) {
+  int w = 1;
+  while (w * 512 < D) w <<= 1;
+  return w;                                               // 1, 2, 4, 8, 16 (D <= 8192)
+}
+
+// workgroups of the backward = rows of partial column sums
+int gated_norm_bwd_blocks(int64_t T, int D) {
+  const int w = bwd_row_waves(D);
+  if (w == 1) {
+    const int64_t need = (T + kBwdWaves - 1) / kBwdWaves;
+    return (int)(need < kMaxBwdBlocks ? need : kMaxBwdBlocks);
+  }
+  const int64_t cap = 256 * (16 / w);                     // 16 waves per compute unit
+  return (int)(T < cap ? T : cap);
 }
 
 template <typename E, int NCH>
@@ -309,9 +408,20 @@ static hipError_t fwd_one(const NormFwdArgs& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
+template <typename E, int W>
+static hipError_t bwd_wide(const NormBwdArgs& p, float* partial, hipStream_t stream) {
+  const int nblk = gated_norm_bwd_blocks(p.T, p.D);
+  hipLaunchKernelGGL((gated_norm_bwd_wide_kernel<E, W>), dim3(nblk), dim3(64 * W), 0, stream, p, partial);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(gated_norm_colsum_kernel, dim3((2 * p.D + 63) / 64), dim3(1024), 0, stream, nblk, p.D, partial,
+                     p.dgamma, p.dbeta);
+  return hipGetLastError();
+}
+
 template <typename E, int NCH>
 static hipError_t bwd_one(const NormBwdArgs& p, float* partial, hipStream_t stream) {
-  const int nblk = gated_norm_bwd_blocks(p.T);
+  const int nblk = gated_norm_bwd_blocks(p.T, p.D);
   auto kern = gated_norm_bwd_kernel<E, NCH>;
   const size_t smem = (size_t)2 * p.D * sizeof(float);
   if (smem > 48 * 1024) {
@@ -385,25 +495,22 @@ hipError_t launch_norm_quant_fwd(const NormFwdArgs& p, void* q, int64_t sq, floa
 }
 
 hipError_t launch_norm_bwd(const NormBwdArgs& p, float* partial, hipStream_t stream) {
-  const int nch = chunks_per_lane(p.D);
-#define BWD_CALL(E, N) bwd_one<E, N>(p, partial, stream)
-  if (p.dtype == 0) {
-    switch (nch) {
-      case 1: return BWD_CALL(__bf16, 1);
-      case 2: return BWD_CALL(__bf16, 2);
-      case 4: return BWD_CALL(__bf16, 4);
-      case 8: return BWD_CALL(__bf16, 8);
-      default: return BWD_CALL(__bf16, 16);
-    }
+  if (p.T <= 0) {                                          // no rows: the column sums are zero
+    hipLaunchKernelGGL(gated_norm_colsum_kernel, dim3((2 * p.D + 63) / 64), dim3(1024), 0, stream, 0, p.D, partial, p.dgamma, p.dbeta);
+    return hipGetLastError();
   }
-  switch (nch) {
-    case 1: return BWD_CALL(float, 1);
-    case 2: return BWD_CALL(float, 2);
-    case 4: return BWD_CALL(float, 4);
-    case 8: return BWD_CALL(float, 8);
-    default: return BWD_CALL(float, 16);
+  const int w = bwd_row_waves(p.D);
+#define BWD_WIDE(E)                                        \
+  switch (w) {                                             \
+    case 1: return bwd_one<E, 1>(p, partial, stream);      \
+    case 2: return bwd_wide<E, 2>(p, partial, stream);     \
+    case 4: return bwd_wide<E, 4>(p, partial, stream);     \
+    case 8: return bwd_wide<E, 8>(p, partial, stream);     \
+    default: return bwd_wide<E, 16>(p, partial, stream);   \
   }
-#undef BWD_CALL
+  if (p.dtype == 0) { BWD_WIDE(__bf16) }
+  BWD_WIDE(float)
+#undef BWD_WIDE
 }
 
 // contiguous [T, D] tensors, statistics computed: the form behind the C entry points

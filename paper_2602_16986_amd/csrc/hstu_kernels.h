@@ -109,8 +109,8 @@ hipError_t launch_norm_fwd(const NormFwdArgs& p, hipStream_t stream);
 // same rows as launch_norm_fwd (p.y unused; p.gamma == nullptr: no normalisation), written as E4M3 codes q [T, D] (row stride
 // sq bytes) with one fp32 scale per row
 hipError_t launch_norm_quant_fwd(const NormFwdArgs& p, void* q, int64_t sq, float* qscale, hipStream_t stream);
-hipError_t launch_norm_bwd(const NormBwdArgs& p, float* partial, hipStream_t stream);   // partial: gated_norm_bwd_blocks(T) x 2 x D floats
-int gated_norm_bwd_blocks(int64_t T);
+hipError_t launch_norm_bwd(const NormBwdArgs& p, float* partial, hipStream_t stream);   // partial: gated_norm_bwd_blocks(T, D) x 2 x D floats
+int gated_norm_bwd_blocks(int64_t T, int D);
 hipError_t launch_gated_norm_fwd(int64_t T, int D, int dtype, const void* attn, const void* u, const float* gamma,
                                  const float* beta, float eps, void* y, float* mean, float* rstd, hipStream_t stream);
 hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, const void* attn, const void* u,

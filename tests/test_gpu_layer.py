@@ -74,6 +74,11 @@ def test_layer_small(hb, name):
     run_case(wl.layer_case(name))
 
 
+def test_layer_wide_rows(hb):
+    """Embedding width and H d above 512: both norms' backward passes share a row among the waves of a workgroup."""
+    run_case(wl.build_layer("layer-wide", [70, 0, 33, 129], 8, 128, 1024, seed=3, K1=40, K2=8))
+
+
 def test_layer_mid(hb):
     """Four sequences of 1024..2048 tokens, H=4, d=128, E=512: the layer shape of the benchmark at a size the oracle
     finishes in seconds."""

@@ -117,7 +117,8 @@ def test_empty_batch_and_errors(hb):
     assert e.value.status == -2
 
 
-@pytest.mark.parametrize("dtype,D", [("bf16", 256), ("bf16", 1024), ("fp32", 64), ("bf16", 520), ("bf16", 4096)])
+@pytest.mark.parametrize("dtype,D", [("bf16", 256), ("bf16", 1024), ("fp32", 64), ("bf16", 520), ("bf16", 4096),
+                                      ("bf16", 1536), ("bf16", 2048), ("fp32", 1032), ("bf16", 8192), ("fp32", 4104)])
 def test_gated_norm(hb, dtype, D):
     rng = np.random.default_rng(1)
     T = 301
