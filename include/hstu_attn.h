@@ -103,12 +103,16 @@ typedef struct hstu_attn_params {
  * batch, num_heads, head_dim, total_tokens, max_seqlen and dtype.  Returns 0 for an
  * invalid description (the compute call then reports the error).  The backward figure
  * includes fp32 partial-sum slots for key blocks that the scheduler cuts along the query
- * axis (at most 768 x 2 x 128 x head_dim floats, about 100 MB at head_dim 128). */
+ * axis (at most 768 x 2 x 128 x head_dim floats, about 100 MB at head_dim 128); the forward figure includes the same kind
+ * of slots for query blocks cut along the key axis (at most 768 x 128 x head_dim floats, 50 MB at head_dim 128). */
 size_t hstu_attn_workspace_bytes(const hstu_attn_params* p, int for_backward);
 
 /* Paper Eq. 3, forward (attention_forward of the appendix pseudocode).
  * q, k, v: inputs [T, H, d]; out: A [T, H, d]; all DEVICE, dtype p->dtype.
- * Enqueues: tile scheduler (skips fully masked blocks), bias expansion, attention kernel. */
+ * Enqueues: tile scheduler (skips fully masked blocks), bias expansion, attention kernel, combine kernel.
+ * A query block whose list of key tiles is longer than a workgroup slot's share of the whole batch (small batches: one
+ * long sequence, a few short ones) is cut into equal pieces along the key axis; the pieces write fp32 partial sums into
+ * the workspace and the combine kernel adds them in piece order (deterministic) and writes the rows. */
 int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, void* out,
                   void* workspace, size_t workspace_bytes, void* stream);
 

@@ -38,9 +38,9 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
     const int rows = !for_backward ? fwd_block_rows(p->dtype, p->head_dim)
                                    : (s == 0 ? dq_block_rows(p->dtype, p->head_dim) : dkv_block_rows(p->dtype, p->head_dim));
     l.max_items[s] = (int)max_items_for(p, rows);
-    // the dK/dV list also holds the pieces of cut key blocks; so does the forward list over a query tail (few query
-    // blocks against long histories: their key axis is cut)
-    if ((for_backward && s == 1) || (!for_backward && p->query_tail > 0)) {
+    // the dK/dV list also holds the pieces of cut key blocks; so does the forward list (query blocks longer than a
+    // workgroup slot's share of the batch, or the few blocks of a query tail against long histories: their key axis is cut)
+    if ((for_backward && s == 1) || !for_backward) {
       l.slot_cap = slot_cap_for(l.max_items[s]);
       l.max_items[s] += l.slot_cap;
     }
@@ -50,7 +50,7 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
   }
   l.bias = off;
   off += align_up((size_t)p->num_heads * ((size_t)p->max_seqlen + 1) * sizeof(float));
-  if (!for_backward && p->query_tail > 0) {
+  if (!for_backward) {
     l.splits = off; off += align_up((size_t)(l.slot_cap / 2 + 1) * sizeof(SplitItem));
     l.partial = off;
     off += align_up((size_t)l.slot_cap * fwd_block_rows(p->dtype, p->head_dim) * p->head_dim * sizeof(float));
@@ -214,16 +214,13 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
   a.max_items = l.max_items[0];
   a.header = (const SchedHeader*)(ws + l.header[0]);
   a.items = (const WorkItem*)(ws + l.items[0]);
-  const bool tail = p->query_tail > 0;
-  if (tail) {
-    a.splits = (const SplitItem*)(ws + l.splits);
-    a.partial = (float*)(ws + l.partial);
-  }
+  a.splits = (const SplitItem*)(ws + l.splits);
+  a.partial = (float*)(ws + l.partial);
   {
     ProfScope ps("schedule_fwd", stream);
     if (launch_schedule(a, fwd_block_rows(p->dtype, p->head_dim), fwd_tile_rows(p->dtype, p->head_dim), false,
                         (SchedHeader*)(ws + l.header[0]), (WorkItem*)(ws + l.items[0]), (int32_t*)(ws + l.seq_base[0]),
-                        tail ? (SplitItem*)(ws + l.splits) : nullptr, tail ? l.slot_cap : 0, stream) != hipSuccess)
+                        (SplitItem*)(ws + l.splits), l.slot_cap, stream) != hipSuccess)
       return HSTU_ERR_LAUNCH;
   }
   {
@@ -231,9 +228,9 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
     if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   {
-    ProfScope ps("attn_fwd", stream);                      // with a query tail: includes the kernel that combines the pieces
+    ProfScope ps("attn_fwd", stream);                      // includes the kernel that combines the pieces of cut blocks
     if (launch_attn_fwd(a, p->dtype, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
-    if (tail && launch_fwd_combine(a, p->dtype, l.slot_cap / 2, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    if (launch_fwd_combine(a, p->dtype, l.slot_cap / 2, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   return HSTU_OK;
 }

@@ -23,12 +23,15 @@ constexpr int kSeqCache = 1024;      // batches up to this size keep their block
 constexpr int kItemsPerThread = kSortMax / kSchedThreads;
 constexpr int kMinChunk = 8;         // a long key block is cut into pieces of at least this many tiles ...
 constexpr int kTargetChunks = 2048;  // ... and of about 1/2048 of all scheduled tiles (4 per workgroup slot of the chip)
+constexpr int kFwdTargetChunks = 1536;   // forward lists: 2 x chunk = one slot's share when 768 workgroups are resident
 
 // One workgroup builds one list; the backward pass launches two (dQ blocks and dK/dV blocks) side by side.
 struct SchedJob {
   int block_rows, tile_cols, key_major;
   int query_tail;                     // > 0 (query-major lists only): only the blocks that hold the last query_tail history rows or candidates
   int slot_cap;            // > 0: blocks much longer than the average may be cut along the streamed axis
+  int even;                // cut blocks into equal pieces of at most 2 x chunk tiles (else: pieces of chunk tiles)
+  int target_chunks;       // chunk = all scheduled tiles / target_chunks (at least kMinChunk)
   SchedHeader* header;
   WorkItem* items;
   int32_t* seq_base;
@@ -186,7 +189,16 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   // lists only: the few key blocks of a global prefix are seen by every query of their sequence).  Each piece
   // becomes an entry of the list and accumulates into a partial-sum slot of its own (one per head).  The piece size
   // doubles until the slots and the list fit.  Packed counters, per pair: entries | slots << 20 | cut pairs << 40.
-  int chunk = (int)min((unsigned long long)0x3FFFFFFF, max((unsigned long long)kMinChunk, (all_tiles + kTargetChunks - 1) / kTargetChunks));
+  int chunk = (int)min((unsigned long long)0x3FFFFFFF,
+                       max((unsigned long long)kMinChunk, (all_tiles + job.target_chunks - 1) / (unsigned long long)job.target_chunks));
+  // pieces of a block of `cost` tiles and their length: key-major lists take pieces of `chunk` tiles (a block of a global
+  // prefix is hundreds of times longer than the rest); query-major lists, where the longest block is a few slot shares at
+  // most, take the fewest equal pieces of at most 2 x chunk tiles (every piece costs a partial-sum slot and its traffic)
+  auto pieces_of = [&](int cost, int ch) {
+    if (!(job.slot_cap > 0 && cost > 2 * ch)) return 1;
+    return job.even ? (cost + 2 * ch - 1) / (2 * ch) : (cost + ch - 1) / ch;
+  };
+  auto piece_len = [&](int cost, int pieces, int ch) { return job.even ? (cost + pieces - 1) / pieces : ch; };
   unsigned long long excl = (unsigned long long)min(tid * ipt, pairs), sum = (unsigned long long)pairs;
   while (job.slot_cap > 0) {                               // no slots: one entry per item, in natural order
     unsigned long long mine = 0;
@@ -195,8 +207,8 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
       const int idx = tid * ipt + k;
       if (k < ipt && idx < pairs) {
         const int cost = my_cost[k];
-        const bool cut = job.slot_cap > 0 && cost > 2 * chunk;
-        const unsigned long long pieces = cut ? (unsigned long long)((cost + chunk - 1) / chunk) : 1ull;
+        const unsigned long long pieces = (unsigned long long)pieces_of(cost, chunk);
+        const bool cut = pieces > 1;
         mine += pieces | (cut ? (pieces << 20) | (1ull << 40) : 0ull);
       }
     }
@@ -214,12 +226,12 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
       const int idx = tid * ipt + k;
       if (k < ipt && idx < pairs) {
         const int cost = my_cost[k];
-        const bool cut = job.slot_cap > 0 && cost > 2 * chunk;
-        const int pieces = cut ? (cost + chunk - 1) / chunk : 1;
+        const int pieces = pieces_of(cost, chunk), plen = piece_len(cost, pieces, chunk);
+        const bool cut = pieces > 1;
         slot_c[idx] = cut ? (uint16_t)slot : (uint16_t)0xFFFF;
         for (int c = 0; c < pieces; ++c) {
           // ties keep the natural order of the pairs (sequence-major, last block first)
-          const uint32_t pc = (uint32_t)min(cut ? min(chunk, cost - c * chunk) : cost, 0x7FFFF);
+          const uint32_t pc = (uint32_t)min(cut ? min(plen, cost - c * plen) : cost, 0x7FFFF);
           keys[e + c] = ((0x7FFFFu - pc) << 13) | (uint32_t)(e + c);      // entry < 8192 = 2^13
           entry_item[e + c] = (uint32_t)idx | ((uint32_t)c << 13);
         }
@@ -284,16 +296,19 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     const bool cut = slot_c[idx] != 0xFFFF;
     int b, rb, h, cost = 0, dense;
     locate(idx, 1, b, rb, h, cost, dense, cut);
-    const int pieces = cut ? (cost + chunk - 1) / chunk : 1;
-    items[e] = cut ? WorkItem{b, (rb << 8) | hh, c * chunk, min((c + 1) * chunk, cost), (int)slot_c[idx] * H + hh * pieces + c, 0}
+    const int pieces = cut ? pieces_of(cost, chunk) : 1, plen = piece_len(cost, pieces, chunk);
+    items[e] = cut ? WorkItem{b, (rb << 8) | hh, c * plen, min((c + 1) * plen, cost), (int)slot_c[idx] * H + hh * pieces + c, 0}
                    : WorkItem{b, (rb << 8) | hh, 0, 0x7FFFFFFF, -1, 0};
   }
 }
 
 hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, bool key_major, SchedHeader* header,
                            WorkItem* items, int32_t* seq_base, SplitItem* splits, int slot_cap, hipStream_t stream) {
-  const SchedJob job = {block_rows, tile_cols, key_major ? 1 : 0, key_major ? 0 : a.query_tail, splits ? slot_cap : 0, header, items,
-                        seq_base, splits};
+  // forward lists (query-major): equal pieces of about one workgroup slot's share (768 slots at three workgroups per compute
+  // unit); the forward over a query tail keeps the finer pieces of the key-major lists (few blocks, each against a whole history)
+  const bool even = !key_major && a.query_tail == 0;
+  const SchedJob job = {block_rows, tile_cols, key_major ? 1 : 0, key_major ? 0 : a.query_tail, splits ? slot_cap : 0, even ? 1 : 0,
+                        even ? kFwdTargetChunks : kTargetChunks, header, items, seq_base, splits};
   hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
                      a.K2, job, job);
   return hipGetLastError();
@@ -302,8 +317,8 @@ hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, boo
 hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
                                 WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* splits, int slot_cap,
                                 hipStream_t stream) {
-  const SchedJob j0 = {block_rows[0], tile_cols[0], 0, 0, 0, header[0], items[0], seq_base[0], nullptr};
-  const SchedJob j1 = {block_rows[1], tile_cols[1], 1, 0, slot_cap, header[1], items[1], seq_base[1], splits};
+  const SchedJob j0 = {block_rows[0], tile_cols[0], 0, 0, 0, 0, kTargetChunks, header[0], items[0], seq_base[0], nullptr};
+  const SchedJob j1 = {block_rows[1], tile_cols[1], 1, 0, slot_cap, 0, kTargetChunks, header[1], items[1], seq_base[1], splits};
   hipLaunchKernelGGL(schedule_kernel, dim3(2), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
                      a.K2, j0, j1);
   return hipGetLastError();

@@ -283,14 +283,16 @@ def test_forward_query_tail(hb, name, tail):
 
 
 def test_schedule_is_a_longest_first_permutation(hb):
-    """The forward work list of a dense batch, read back from the workspace: every (sequence, row block, head) exactly once.
-    The list is made of groups of 4 (sequence, block) pairs, each group written once per head (4 consecutive items share a
-    head); the pairs come with non-increasing cost (tiles of the block: dense causal, no candidates -> last row / 32 + 1),
-    equal costs in natural order (sequence, block descending)."""
+    """The forward work list of a dense batch, read back from the workspace.  Every (sequence, row block, head) appears
+    either once (whole) or as pieces [t0, t1) that tile its list of column tiles exactly, each piece with a partial-sum slot
+    of its own.  The list is made of groups of 4 entries, each group written once per head (4 consecutive items share a
+    head); the entries come with non-increasing cost (tiles of the entry; a whole block of a dense causal batch without
+    candidates has last row / 32 + 1), equal costs in natural order (sequence, block descending, piece)."""
     from paper_2602_16986_amd.runner import DeviceWorkload
     rng = np.random.default_rng(4)
     G = 4
-    for lengths in ([300, 0, 1, 129, 517, 64], rng.integers(1, 3000, size=23).tolist()):
+    some_cut = False
+    for lengths in ([300, 0, 1, 129, 517, 64], rng.integers(1, 3000, size=23).tolist(), [4000]):
         w = wl.build("sched", lengths, 3, 128, "bf16", seed=1)
         dw = DeviceWorkload(w)
         dw.attn_fwd()
@@ -299,19 +301,35 @@ def test_schedule_is_a_longest_first_permutation(hb):
         n = st["items"]
         items = dw.ws_fwd[256:256 + 24 * n].cpu().numpy().view(np.int32).reshape(n, 6)
         BM = 128
-        want = {(b, rb, h) for b, L in enumerate(lengths) for rb in range((L + BM - 1) // BM) for h in range(w.H)}
-        got = [(int(b), int(rbh) >> 8, int(rbh) & 255) for b, rbh in items[:, :2]]
-        assert len(got) == len(want) and set(got) == want
+        full = lambda b, rb: (min((rb + 1) * BM, lengths[b]) - 1) // 32 + 1
+        got = [(int(b), int(rbh) >> 8, int(rbh) & 255, int(t0), int(t1), int(slot)) for b, rbh, t0, t1, slot, _ in items]
         assert n % w.H == 0
-        pairs = []
+        # every block covered exactly once
+        cover = {}
+        for b, rb, h, t0, t1, slot in got:
+            cover.setdefault((b, rb, h), []).append((t0, min(t1, full(b, rb)), slot))
+        assert set(cover) == {(b, rb, h) for b, L in enumerate(lengths) for rb in range((L + BM - 1) // BM) for h in range(w.H)}
+        slots = [slot for v in cover.values() for _, _, slot in v if slot >= 0]
+        assert len(slots) == len(set(slots))
+        for (b, rb, h), v in cover.items():
+            v.sort()
+            if len(v) == 1:
+                assert v[0] == (0, full(b, rb), -1)
+            else:
+                some_cut = True
+                assert v[0][0] == 0 and v[-1][1] == full(b, rb) and all(x[1] == y[0] for x, y in zip(v, v[1:]))
+                assert [x[2] for x in v] == list(range(v[0][2], v[0][2] + len(v)))      # consecutive slots in piece order
+        # run structure and order
+        entries = []
         for g0 in range(0, n, G * w.H):
             grp = got[g0:g0 + G * w.H]
             size = len(grp) // w.H
-            first = [(b, rb) for b, rb, h in grp[:size]]
+            first = [(b, rb, t0, t1) for b, rb, h, t0, t1, slot in grp[:size]]
             for h in range(w.H):
-                assert grp[h * size:(h + 1) * size] == [(b, rb, h) for b, rb in first]
-            pairs += first
-        cost = [(min((rb + 1) * BM, lengths[b]) - 1) // 32 + 1 for b, rb in pairs]
-        for (a, ca), (b_, cb) in zip(zip(pairs, cost), zip(pairs[1:], cost[1:])):
-            assert ca > cb or (ca == cb and (a[0], -a[1]) < (b_[0], -b_[1])), "not longest-first with natural ties"
-        assert np.all(items[:, 4] == -1)
+                assert [(b, rb, hh, t0, t1) for b, rb, hh, t0, t1, slot in grp[h * size:(h + 1) * size]] == \
+                       [(b, rb, h, t0, t1) for b, rb, t0, t1 in first]
+            entries += first
+        cost = [min(t1, full(b, rb)) - t0 for b, rb, t0, t1 in entries]
+        for (a, ca), (b_, cb) in zip(zip(entries, cost), zip(entries[1:], cost[1:])):
+            assert ca > cb or (ca == cb and (a[0], -a[1], a[2]) < (b_[0], -b_[1], b_[2])), "not longest-first with natural ties"
+    assert some_cut, "the single long sequence should have had its last blocks cut"
