@@ -96,6 +96,12 @@ typedef struct hstu_attn_params {
                                truncation (Section 4.3: only the rows that survive are needed) and of serving few recent rows
                                against a long history.  hstu_attn_bwd and the layer entry points return HSTU_ERR_UNSUPPORTED
                                when it is set */
+  int32_t reuse_schedule;   /* 0: the call builds its work lists (tile scheduler) in the workspace.  1: the workspace still holds the
+                               lists that the same entry point (hstu_attn_fwd, or hstu_attn_bwd) wrote for the same batch,
+                               num_heads, head_dim, dtype, mask and query_tail, and no other call has used the workspace since: the
+                               scheduler is skipped (the layers of one model share seq_offsets and mask, so only the first layer
+                               of a forward or of a backward sweep needs it).  The bias table is expanded on every call.  The
+                               layer entry points pass it on to their attention calls */
 } hstu_attn_params;
 
 /* Bytes of device scratch (256-byte aligned) that hstu_attn_fwd (for_backward = 0)

@@ -37,7 +37,7 @@ class HstuAttnParams(ctypes.Structure):
         ("local_window", ctypes.c_int32), ("global_prefix", ctypes.c_int32),
         ("alpha", ctypes.c_float), ("inv_n", ctypes.c_float),
         ("rab_table", ctypes.c_void_p), ("rab_bounds", ctypes.c_void_p), ("num_buckets", ctypes.c_int32),
-        ("d_rab_table", ctypes.c_void_p), ("query_tail", ctypes.c_int32),
+        ("d_rab_table", ctypes.c_void_p), ("query_tail", ctypes.c_int32), ("reuse_schedule", ctypes.c_int32),
     ]
 
 
@@ -133,7 +133,7 @@ class AttnProblem:
 
     def __init__(self, q, k, v, out_like, seq_offsets, *, max_seqlen, seq_offsets_host=None, num_targets=None,
                  local_window=-1, global_prefix=0, alpha=1.0, inv_n=1.0, rab_table=None, rab_bounds=None,
-                 d_rab_table=None, query_tail=0):
+                 d_rab_table=None, query_tail=0, reuse_schedule=False):
         T, H, d = q.shape
         self._keep = (seq_offsets, num_targets, rab_table, rab_bounds, d_rab_table)
         self._host = None if seq_offsets_host is None else np.ascontiguousarray(seq_offsets_host, dtype=np.int32)
@@ -153,6 +153,7 @@ class AttnProblem:
         p.num_buckets = 0 if rab_bounds is None else int(rab_bounds.shape[0])
         p.d_rab_table = _ptr(d_rab_table)          # fp32 [H, num_buckets] output of hstu_attn_bwd, or None
         p.query_tail = int(query_tail)             # forward only: compute the last rows of every sequence only
+        p.reuse_schedule = int(bool(reuse_schedule))   # the workspace still holds this entry point's work lists for this batch
         self.params = p
 
     def ref(self):

@@ -88,6 +88,7 @@ int validate(const hstu_attn_params* p) {
   if (p->rab_table && (p->num_buckets < 1 || p->num_buckets > 4096)) return HSTU_ERR_SHAPE;
   if (p->d_rab_table && !p->rab_table) return HSTU_ERR_NULL;
   if (p->query_tail < 0) return HSTU_ERR_SHAPE;
+  if (p->reuse_schedule != 0 && p->reuse_schedule != 1) return HSTU_ERR_SHAPE;
   if ((int64_t)p->total_tokens * p->num_heads / 32 + (int64_t)p->batch * p->num_heads > 0x7FFFFF00) return HSTU_ERR_SHAPE;
   if (p->seq_offsets_host) {
     const int32_t* o = p->seq_offsets_host;
@@ -216,7 +217,7 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
   a.items = (const WorkItem*)(ws + l.items[0]);
   a.splits = (const SplitItem*)(ws + l.splits);
   a.partial = (float*)(ws + l.partial);
-  {
+  if (!p->reuse_schedule) {
     ProfScope ps("schedule_fwd", stream);
     if (launch_schedule(a, fwd_block_rows(p->dtype, p->head_dim), fwd_tile_rows(p->dtype, p->head_dim), false,
                         (SchedHeader*)(ws + l.header[0]), (WorkItem*)(ws + l.items[0]), (int32_t*)(ws + l.seq_base[0]),
@@ -262,7 +263,7 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
     ProfScope ps("bias_expand", stream);
     if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
-  {
+  if (!p->reuse_schedule) {
     ProfScope ps("schedule_bwd", stream);
     const int rows[2] = {dq_block_rows(p->dtype, p->head_dim), dkv_block_rows(p->dtype, p->head_dim)};
     const int cols[2] = {tile, dkv_tile_rows(p->dtype, p->head_dim)};

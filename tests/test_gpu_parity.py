@@ -333,3 +333,40 @@ def test_schedule_is_a_longest_first_permutation(hb):
         for (a, ca), (b_, cb) in zip(zip(entries, cost), zip(entries[1:], cost[1:])):
             assert ca > cb or (ca == cb and (a[0], -a[1], a[2]) < (b_[0], -b_[1], b_[2])), "not longest-first with natural ties"
     assert some_cut, "the single long sequence should have had its last blocks cut"
+
+
+def test_reuse_schedule_gives_identical_results(hb):
+    """A second forward (backward) that reuses the work lists of the first in the same workspace, on new tensors of the
+    same batch (the next layer of a model): bit-identical to a call that builds its own lists; a value other than 0/1 is
+    rejected."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    for name in ("bf16-sparse", "bf16-targets"):
+        w = wl.small(name)
+        dw = DeviceWorkload(w)
+        dw.attn_fwd()
+        dw.attn_bwd()
+        torch.cuda.synchronize()
+        # "next layer": other values, same geometry
+        q2, k2, v2 = (t.flip(0).contiguous() for t in (dw.q, dw.k, dw.v))
+        outs = []
+        for reuse in (0, 1):
+            out = torch.full_like(dw.out, float("nan"))
+            dw.attn_fwd()                                   # leaves this problem's forward lists in ws_fwd
+            dw.problem.params.reuse_schedule = reuse
+            hb.hstu_attn_fwd(dw.problem, q2, k2, v2, out, dw.ws_fwd)
+            dq, dk, dv = (torch.full_like(t, float("nan")) for t in (dw.q, dw.k, dw.v))
+            dw.problem.params.reuse_schedule = 0
+            dw.attn_bwd()                                   # this problem's backward lists in ws_bwd
+            dw.problem.params.reuse_schedule = reuse
+            hb.hstu_attn_bwd(dw.problem, q2, k2, v2, dw.dout, dq, dk, dv, dw.ws_bwd)
+            torch.cuda.synchronize()
+            dw.problem.params.reuse_schedule = 0
+            outs.append((out, dq, dk, dv))
+        for a, b in zip(*outs):
+            assert not torch.isnan(a.float()).any()
+            assert torch.equal(a, b)
+    dw.problem.params.reuse_schedule = 2
+    with pytest.raises(hb.HstuError) as e:
+        hb.hstu_attn_fwd(dw.problem, dw.q, dw.k, dw.v, dw.out, dw.ws_fwd)
+    assert e.value.status == -2
+    dw.problem.params.reuse_schedule = 0
