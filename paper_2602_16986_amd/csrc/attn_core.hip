@@ -569,8 +569,8 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
         // Mixed tile whose (existing) query rows are all history rows: every visible pair has distance i - j >= 0, which is
         // what the strip is indexed by, so the scores are seeded like a full tile's and only the mask is applied
         // per element (no table gathers, whose wait would also wait for the tile being fetched).
-        // (Query-stationary passes only: in the dK/dV pass it measured 2-4 % slower than the gathers.)
-        const bool seeded = MODE != kBwdDKDV && kind == kTilePartial && bias_h && min(xw0 + 32, L) - 1 < g.n;
+        // In the dK/dV pass the query rows are the streamed tile's.
+        const bool seeded = kind == kTilePartial && min((MODE == kBwdDKDV ? y0 + C::BN : xw0 + 32), L) - 1 < g.n;
         if ((kind == kTileFull || seeded) && bias_h) {
           // the distance of every pair that counts is >= 0: seed the accumulators with the bias strip
           const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
@@ -674,16 +674,65 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
               c2[u][r] = vis ? p : 0.f;
             }
           };
-          if (seeded) {
+          if (seeded && MODE == kBwdDKDV) {
+            // History rows only, seen from key x: the queries y >= x with y - x < K1 (any y >= x for a key of the global
+            // prefix or a dense mask), and y < L.  Query = y0 + c + 4 hf, c a compile-time constant per register.
+            const int lo = (x_ok ? x - y0 : (1 << 30)) - 4 * hf;                              // c >= lo  <=>  y >= x
+            const int band = (g.K1 < 0 || x < g.K2) ? (1 << 30) : x + g.K1 - 1 - y0;           // last query of the band
+            const int up = min(band, L - 1 - y0) - 4 * hf;                                     // c <= up
+            const int kfirst = max(xw0, g.K2);                                                 // first key of the wave outside the prefix
+            const bool need_lo = y0 < min(xw0 + 31, L - 1);
+            const bool need_up = y0 + C::BN > L || (g.K1 >= 0 && kfirst <= xw0 + 31 && y0 + C::BN - 1 - kfirst >= g.K1);
+            if (need_lo && !need_up) {
 #pragma unroll
-            for (int u = 0; u < SBG; ++u)
+              for (int u = 0; u < SBG; ++u)
 #pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                const int y = y0 + (sg + u) * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-                int delta;
-                const bool vis = (MODE == kBwdDKDV) ? visible(g, y, x, delta) : visible(g, x, y, delta);
-                mixed(u, r, sc1[u][r], vis);
-              }
+                for (int r = 0; r < 16; ++r) mixed(u, r, sc1[u][r], (sg + u) * 32 + 8 * (r >> 2) + (r & 3) >= lo);
+            } else if (need_up && !need_lo) {
+#pragma unroll
+              for (int u = 0; u < SBG; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mixed(u, r, sc1[u][r], (sg + u) * 32 + 8 * (r >> 2) + (r & 3) <= up);
+            } else {
+#pragma unroll
+              for (int u = 0; u < SBG; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                  const int c = (sg + u) * 32 + 8 * (r >> 2) + (r & 3);
+                  mixed(u, r, sc1[u][r], c >= lo && c <= up);
+                }
+            }
+          } else if (seeded) {
+            // History rows only: row x sees the keys y <= x with x - y < K1 or y < K2.  Relative to the tile's first key and
+            // to this lane's register pattern (key = y0 + c + 4 hf, c a compile-time constant per register) these are three
+            // per-lane bounds, and the ones that cannot bind anywhere in this wave's 32 x BN pairs are dropped for the tile.
+            const int up = (x_ok ? x - y0 : -1) - 4 * hf;                // c <= up   <=>  y <= x (no key for a row past the end)
+            const int lo = x - g.K1 + 1 - y0 - 4 * hf;                    // c >= lo   <=>  x - y < K1
+            const int pre = g.K2 - y0 - 4 * hf;                           // c <  pre  <=>  y < K2
+            const bool need_lo = g.K1 >= 0 && min(xw0 + 31, L - 1) - y0 >= g.K1;
+            const bool need_pre = need_lo && g.K2 > y0;
+            if (!need_lo) {
+#pragma unroll
+              for (int u = 0; u < SBG; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mixed(u, r, sc1[u][r], (sg + u) * 32 + 8 * (r >> 2) + (r & 3) <= up);
+            } else if (!need_pre) {
+#pragma unroll
+              for (int u = 0; u < SBG; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                  const int c = (sg + u) * 32 + 8 * (r >> 2) + (r & 3);
+                  mixed(u, r, sc1[u][r], c <= up && c >= lo);
+                }
+            } else {
+#pragma unroll
+              for (int u = 0; u < SBG; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                  const int c = (sg + u) * 32 + 8 * (r >> 2) + (r & 3);
+                  mixed(u, r, sc1[u][r], c <= up && (c >= lo || c < pre));
+                }
+            }
           } else {
 #pragma unroll
             for (int u = 0; u < SBG; ++u)
