@@ -138,9 +138,14 @@ __device__ __forceinline__ void diag_all(std::integer_sequence<int, R...>, const
 
 // DBIAS (dQ pass only): also sum dS along the diagonals of every tile (pairs of equal distance i - j) into
 // a.dbias_dist[h, distance]; dbias_reduce_kernel folds distances into buckets afterwards.
-template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false>
+// CAND (query-stationary passes, batches with candidate rows): the fast paths also cover candidate rows against history
+// keys.  A candidate row stands at position n for the mask and for the bias, so full and mask-edge tiles of such rows work
+// like those of history rows once the bias strip is addressed with the row's effective position.  Batches without
+// candidates run the instantiation without it (a few scalar instructions per tile less).
+template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false, bool CAND = false>
 __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) void attn_kernel(const AttnArgs a) {
   static_assert(!DBIAS || MODE == kBwdDQ, "the bias gradient rides with the dQ pass");
+  static_assert(!CAND || MODE != kBwdDKDV, "candidate fast paths: query-stationary passes");
   using C = Cfg<E, D, MODE, NWAVES>;
   using RFrag = typename ResidentFrag<E>::type;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -230,7 +235,10 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   const int ntiles = min(tr.count(), item.t1);             // this item's share of the block's tile list is [t_begin, ntiles)
   const float* bias_h = a.bias ? a.bias + (int64_t)h * a.bias_stride : nullptr;
   // this lane's start inside the bias strip: copy c = s0 mod 4 makes its 4-entry reads 16-byte aligned
-  const int strip_s0 = C::BX - 1 - (wave * 32 + l32) + 4 * hf;
+  // Query-stationary passes: a candidate row (x >= n) stands at position n for the mask and for the bias, so the strip is
+  // addressed with the row's effective position px, and a block made of candidates only puts the strip's origin at n.
+  const int x0v = CAND ? min(x0, g.n) : x0;
+  const int strip_s0 = C::BX - 1 - ((CAND ? min(x, g.n) : x) - x0v) + 4 * hf;
   const int strip_lane = (strip_s0 & 3) * C::SLEN + (strip_s0 & ~3);
 
   // ---- staging of the streamed tiles: global -> LDS directly, or through registers
@@ -303,7 +311,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     nx_a1 = (uint64_t)(uintptr_t)Y1 + (uint64_t)(uint32_t)yrow * rowb1;
     nx_a2 = (uint64_t)(uintptr_t)Y2 + (uint64_t)(uint32_t)yrow * rowb2;
     nx_left = valid ? L - yrow : 0;
-    nx_d0x4 = 4 * ((MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) : x0 + (C::BX - 1) - yt * C::BN);
+    nx_d0x4 = 4 * ((MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) : x0v + (C::BX - 1) - yt * C::BN);
     nx_bias_bytes = valid ? (uint32_t)a.bias_stride * 4u : 0u;
   };
   const uint64_t bias_addr = (uint64_t)(uintptr_t)bias_h;
@@ -412,6 +420,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   lstore(0);
   __syncthreads();
 
+  const bool stat_hist = min(xw0 + 32, L) - 1 < g.n;  // this wave's stationary rows are all history rows
   constexpr int NSB = C::BN / 32;                     // 32-row sub-blocks of a streamed tile
   constexpr int SBG = (MODE == kFwd && NSB >= 2) ? 2 : 1;   // sub-blocks whose products are interleaved
   for (int t = t_begin; t < ntiles; ++t) {
@@ -428,8 +437,11 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
 
     // How this wave's 32 stationary rows relate to the tile: nothing visible (skip), everything
     // visible (no mask arithmetic, bias from the strip), or mixed (generic per-element path).
-    int kind = (MODE == kBwdDKDV) ? classify_tile(g, y0, y0 + C::BN - 1, xw0, xw0 + 31)
-                                  : classify_tile(g, xw0, xw0 + 31, y0, y0 + C::BN - 1);
+    // Fully visible tiles of candidate rows (all at position n) against history keys are recognised in the query-stationary
+    // passes only (the dK/dV pass has no strip by the distance n - key), and not with the bias gradient, which adds the dS of
+    // candidate rows to the table by that distance one by one: those take the masked path.
+    int kind = (MODE == kBwdDKDV) ? classify_tile(g, y0, y0 + C::BN - 1, xw0, xw0 + 31, false)
+                                  : classify_tile(g, xw0, xw0 + 31, y0, y0 + C::BN - 1, CAND && !DBIAS);
     if (xw0 >= L || xw0 + 31 < q0) kind = kTileEmpty;
 
     // The next tile's global loads are issued piecewise between the score products: the compute unit's
@@ -570,7 +582,10 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
         // what the strip is indexed by, so the scores are seeded like a full tile's and only the mask is applied
         // per element (no table gathers, whose wait would also wait for the tile being fetched).
         // In the dK/dV pass the query rows are the streamed tile's.
-        const bool seeded = kind == kTilePartial && min((MODE == kBwdDKDV ? y0 + C::BN : xw0 + 32), L) - 1 < g.n;
+        // In the query-stationary passes candidate rows against history keys work the same way with the rows' effective
+        // position n.  (In the dK/dV pass a strip by the distance n - key would be needed: those tiles stay on the general path.)
+        const bool tile_hist = min(y0 + C::BN, L) - 1 < g.n;                 // the streamed rows are all history
+        const bool seeded = kind == kTilePartial && (MODE == kBwdDKDV ? tile_hist : (stat_hist || (CAND && tile_hist)));
         if ((kind == kTileFull || seeded) && bias_h) {
           // the distance of every pair that counts is >= 0: seed the accumulators with the bias strip
           const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
@@ -706,10 +721,12 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
             // History rows only: row x sees the keys y <= x with x - y < K1 or y < K2.  Relative to the tile's first key and
             // to this lane's register pattern (key = y0 + c + 4 hf, c a compile-time constant per register) these are three
             // per-lane bounds, and the ones that cannot bind anywhere in this wave's 32 x BN pairs are dropped for the tile.
-            const int up = (x_ok ? x - y0 : -1) - 4 * hf;                // c <= up   <=>  y <= x (no key for a row past the end)
-            const int lo = x - g.K1 + 1 - y0 - 4 * hf;                    // c >= lo   <=>  x - y < K1
+            // (a candidate row stands at px = n; then the tile holds history keys only and the first bound never binds)
+            const int px = CAND ? min(x, g.n) : x;
+            const int up = (x_ok ? px - y0 : -1) - 4 * hf;               // c <= up   <=>  y <= x (no key for a row past the end)
+            const int lo = px - g.K1 + 1 - y0 - 4 * hf;                   // c >= lo   <=>  x - y < K1
             const int pre = g.K2 - y0 - 4 * hf;                           // c <  pre  <=>  y < K2
-            const bool need_lo = g.K1 >= 0 && min(xw0 + 31, L - 1) - y0 >= g.K1;
+            const bool need_lo = g.K1 >= 0 && min(min(xw0 + 31, L - 1), g.n) - y0 >= g.K1;
             const bool need_pre = need_lo && g.K2 > y0;
             if (!need_lo) {
 #pragma unroll
@@ -910,10 +927,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttnArgs a, int bloc
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false>
+template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false, bool CAND = false>
 static hipError_t launch_one(const AttnArgs& a, hipStream_t stream) {
   using C = Cfg<E, D, MODE, NWAVES>;
-  auto kern = attn_kernel<E, D, MODE, NWAVES, DBIAS>;
+  auto kern = attn_kernel<E, D, MODE, NWAVES, DBIAS, CAND>;
   constexpr int smem_bytes = C::SMEM_BYTES + (DBIAS ? C::DACC_BYTES : 0);
   static bool attr_set[64] = {};                                         // per instantiation and device
   int dev = 0;
@@ -930,19 +947,19 @@ static hipError_t launch_one(const AttnArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <int MODE, int NW_BF16, int NW_FP32, bool DBIAS = false>
+template <int MODE, int NW_BF16, int NW_FP32, bool DBIAS = false, bool CAND = false>
 static hipError_t dispatch(const AttnArgs& a, int dtype, hipStream_t stream) {
   if (dtype == 0) {
     switch (a.D) {
-      case 32: return launch_one<__bf16, 32, MODE, NW_BF16, DBIAS>(a, stream);
-      case 64: return launch_one<__bf16, 64, MODE, NW_BF16, DBIAS>(a, stream);
-      case 128: return launch_one<__bf16, 128, MODE, NW_BF16, DBIAS>(a, stream);
+      case 32: return launch_one<__bf16, 32, MODE, NW_BF16, DBIAS, CAND>(a, stream);
+      case 64: return launch_one<__bf16, 64, MODE, NW_BF16, DBIAS, CAND>(a, stream);
+      case 128: return launch_one<__bf16, 128, MODE, NW_BF16, DBIAS, CAND>(a, stream);
     }
   } else {
     switch (a.D) {
-      case 32: return launch_one<float, 32, MODE, NW_FP32, DBIAS>(a, stream);
-      case 64: return launch_one<float, 64, MODE, NW_FP32, DBIAS>(a, stream);
-      case 128: return launch_one<float, 128, MODE, NW_FP32, DBIAS>(a, stream);
+      case 32: return launch_one<float, 32, MODE, NW_FP32, DBIAS, CAND>(a, stream);
+      case 64: return launch_one<float, 64, MODE, NW_FP32, DBIAS, CAND>(a, stream);
+      case 128: return launch_one<float, 128, MODE, NW_FP32, DBIAS, CAND>(a, stream);
     }
   }
   return hipErrorInvalidValue;
@@ -960,10 +977,13 @@ int fwd_tile_rows(int dtype, int D) { return dtype == 0 ? (D == 128 ? 32 : 64) :
 int dkv_tile_rows(int dtype, int D) { return dtype == 0 ? (D == 128 ? 32 : 64) : 32; }
 
 hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream) {
+  if (a.num_targets) return dispatch<kFwd, kFwdWavesBf16, kFwdWavesFp32, false, true>(a, dtype, stream);
   return dispatch<kFwd, kFwdWavesBf16, kFwdWavesFp32>(a, dtype, stream);
 }
 hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream) {
+  if (a.dbias_dist && a.num_targets) return dispatch<kBwdDQ, kDqWavesBf16, kDqWavesFp32, true, true>(a, dtype, stream);
   if (a.dbias_dist) return dispatch<kBwdDQ, kDqWavesBf16, kDqWavesFp32, true>(a, dtype, stream);
+  if (a.num_targets) return dispatch<kBwdDQ, kDqWavesBf16, kDqWavesFp32, false, true>(a, dtype, stream);
   return dispatch<kBwdDQ, kDqWavesBf16, kDqWavesFp32>(a, dtype, stream);
 }
 

@@ -59,7 +59,8 @@ extern "C" int geometry_check(int L, int M, int K1, int K2, int block_rows, int 
           int delta = 0;
           const bool vis = visible(g, i, j, delta);
           nvis += vis;
-          if (!vis || delta != i - j || i >= g.n || j >= L) ++nbad;
+          const int p = i < g.n ? i : g.n;                       // a candidate row stands at position n
+          if (!vis || delta != p - j || i >= L || j >= L) ++nbad;
         }
       if (kind == kTileFull && nbad) return 70;
       if (kind == kTileEmpty && nvis) return 80;

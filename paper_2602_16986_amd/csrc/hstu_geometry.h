@@ -115,12 +115,17 @@ HSTU_HD TileRanges row_tile_ranges(const SeqGeom& g, int k0, int k1, int BN) {
 // How a block of query rows [w0, w1] relates to a key tile [j0, j1] (j1 may exceed L-1).
 enum TileKind { kTileEmpty = 0, kTileFull = 1, kTilePartial = 2 };
 
-HSTU_HD int classify_tile(const SeqGeom& g, int w0, int w1, int j0, int j1) {
+// cand_rows: also recognise blocks of candidate rows (all at position n) against history keys as empty or full; without
+// it they are reported as partial (for callers whose fast paths assume the distance i - j).
+HSTU_HD int classify_tile(const SeqGeom& g, int w0, int w1, int j0, int j1, bool cand_rows = true) {
   if (w0 >= g.L) return kTileEmpty;
   if (w1 < g.n) {                                            // history rows only, all valid
     if (j0 > w1) return kTileEmpty;
     if (g.K1 >= 0 && w0 - j1 >= g.K1 && j0 >= g.K2) return kTileEmpty;
     if (j1 <= w0 && (g.K1 < 0 || w1 - j0 < g.K1 || j1 < g.K2)) return kTileFull;
+  } else if (cand_rows && w0 >= g.n && j1 < g.n) {           // candidate rows only (all at position n), history keys only
+    if (g.K1 >= 0 && g.n - j1 >= g.K1 && j0 >= g.K2) return kTileEmpty;
+    if (w1 < g.L && (g.K1 < 0 || g.n - j0 < g.K1 || j1 < g.K2)) return kTileFull;
   }
   return kTilePartial;
 }
