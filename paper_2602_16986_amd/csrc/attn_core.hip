@@ -424,7 +424,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   constexpr int NSB = C::BN / 32;                     // 32-row sub-blocks of a streamed tile
   constexpr int SBG = (MODE == kFwd && NSB >= 2) ? 2 : 1;   // sub-blocks whose products are interleaved
   for (int t = t_begin; t < ntiles; ++t) {
-    const int yt = tr.at(t);
+    const int yt = nx_yt;                                    // set_next() of the previous round (or of the prologue) named this tile
     const int stage = (t - t_begin) & 1;
     const bool has_next = t + 1 < ntiles;
     set_next(has_next ? tr.at(t + 1) : 0, has_next);
@@ -598,10 +598,11 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
               sc1[u][4 * q4 + 2] = bv[2]; sc1[u][4 * q4 + 3] = bv[3];
             }
         } else {
+          // (opaque moves: otherwise the compiler clears the registers ahead of the branch, on the strip's path too)
 #pragma unroll
           for (int u = 0; u < SBG; ++u)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sc1[u][r] = 0.f;
+            for (int r = 0; r < 16; ++r) asm volatile("v_mov_b32 %0, 0" : "=v"(sc1[u][r]));
         }
         if constexpr (MODE != kFwd) {
 #pragma unroll
