@@ -148,7 +148,8 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   static_assert(!CAND || MODE != kBwdDKDV, "candidate fast paths: query-stationary passes");
   using C = Cfg<E, D, MODE, NWAVES>;
   using RFrag = typename ResidentFrag<E>::type;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // 256-byte alignment: the fragment reads below form LDS addresses as integers, base included, and XOR the swizzle in
+  extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
 
   // ---- schedule position -> work item.  Workgroups are dealt to the 8 dies round-robin by
   // workgroup id; runs of kXcdGroup consecutive list entries (sorted blocks of one head) are kept on one die.
@@ -458,14 +459,17 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     // 256*R + 2048*hi + (tb ^ (64*ob | 32*hi)).
     const int vchunk = 2 * (grp16 & 1) + ((i16 & 3) >> 1), vbyte = 8 * (i16 & 1);
     const int zl = 4 * (l32 & 3) + ((l32 >> 2) & 3);
-    int kb = stage * C::STAGE_BYTES + l32 * 256 + ((hf ^ (zl & 1)) << 4) + ((zl >> 1) << 5);
-    int tb = stage * C::STAGE_BYTES + (4 * hf + (i16 >> 2)) * 256 + ((i16 >> 2) << 6) + ((vchunk ^ hf) << 4) + vbyte;
+    // (the LDS base rides in kb / tb: reading through `smem + offset` costs an extra vector add per fragment)
+    const int smem_base = (int)(uint32_t)(uintptr_t)(lds_void)smem;
+    int kb = smem_base + stage * C::STAGE_BYTES + l32 * 256 + ((hf ^ (zl & 1)) << 4) + ((zl >> 1) << 5);
+    int tb = smem_base + stage * C::STAGE_BYTES + (4 * hf + (i16 >> 2)) * 256 + ((i16 >> 2) << 6) + ((vchunk ^ hf) << 4) + vbyte;
     asm volatile("" : "+v"(kb), "+v"(tb));
     typedef __attribute__((address_space(3))) short4v* lds_s4;
+    typedef __attribute__((address_space(3))) const bf16x8* lds_b8;
     // row fragment (A operand of a score product): tensor, 32-row sub-block, k-step
     auto rowfrag_at = [&](int tensor, int sub, int ks) -> bf16x8 {
       if constexpr (C::kDma) {
-        return *(const bf16x8*)(smem + (kb ^ (ks << 5)) + sub * 8192 + tensor * C::TILE0);
+        return *(lds_b8)(uintptr_t)(uint32_t)((kb ^ (ks << 5)) + sub * 8192 + tensor * C::TILE0);
       } else {
         return tensor == 0 ? *(const bf16x8*)(y1s + lds_off<C, 0>(sub * 32 + l32, 2 * ks + hf))
                            : *(const bf16x8*)(y2s + lds_off<C, 1>(sub * 32 + l32, 2 * ks + hf));
@@ -476,8 +480,8 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
       short4v lo, hi;
       if constexpr (C::kDma) {
         const int roff = (sub * 32 + ks2 * 16) * 256 + tensor * C::TILE0;
-        lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (tb ^ (ob << 6)) + roff));
-        hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(smem + (tb ^ ((ob << 6) | 32)) + roff + 2048));
+        lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(uint32_t)((tb ^ (ob << 6)) + roff));
+        hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(uint32_t)((tb ^ ((ob << 6) | 32)) + roff + 2048));
       } else {
         const int trow = sub * 32 + ks2 * 16 + 4 * hf + (i16 >> 2);
         if (tensor == 0) {
@@ -615,7 +619,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
           bf16x8 f1[2][SBG], f2[2][SBG], fs[2];
           // stationary operand 1 when it lives in LDS: B fragment of this wave's row x
           auto statfrag = [&](int ks) -> bf16x8 {
-            return *(const bf16x8*)(smem + ((kb - stage * C::STAGE_BYTES) ^ (ks << 5)) + C::STAT_BASE + wave * 8192);
+            return *(lds_b8)(uintptr_t)(uint32_t)(((kb - stage * C::STAGE_BYTES) ^ (ks << 5)) + C::STAT_BASE + wave * 8192);
           };
           if constexpr (C::kStatLds) fs[0] = statfrag(0);
 #pragma unroll
