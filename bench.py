@@ -24,8 +24,8 @@ PEAK_HBM_GBS = 8000.0
 # bytes behind the L2 per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/attention_c3_dense_counters.md (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration
 # against a plain 1 GiB copy); only known for the workload that was profiled
-MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 3.519e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 4.186e9 + 0.090e9,
-                          ("C3-dense", "attn_bwd_dkdv"): 3.083e9 + 0.180e9,
+MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 3.283e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 4.008e9 + 0.090e9,
+                          ("C3-dense", "attn_bwd_dkdv"): 3.266e9 + 0.182e9,
                           # profiles/truncation_at_3072_512.md
                           ("AT-3072-512", "truncate_fwd"): 0.1343e9 + 0.1342e9, ("AT-3072-512", "truncate_bwd"): 0.1343e9 + 0.5240e9,
                           # profiles/fp8_gemm_1m_512.md
