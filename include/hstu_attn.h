@@ -109,8 +109,9 @@ typedef struct hstu_attn_params {
  * batch, num_heads, head_dim, total_tokens, max_seqlen and dtype.  Returns 0 for an
  * invalid description (the compute call then reports the error).  The backward figure
  * includes fp32 partial-sum slots for key blocks that the scheduler cuts along the query
- * axis (at most 768 x 2 x 128 x head_dim floats, about 100 MB at head_dim 128); the forward figure includes the same kind
- * of slots for query blocks cut along the key axis (at most 768 x 128 x head_dim floats, 50 MB at head_dim 128). */
+ * axis (at most 768 x 2 x 128 x head_dim floats, about 100 MB at head_dim 128) and for query blocks that the dQ pass cuts
+ * along the key axis (768 x 128 x head_dim floats); the forward figure includes the same kind of slots for its query blocks
+ * (50 MB at head_dim 128). */
 size_t hstu_attn_workspace_bytes(const hstu_attn_params* p, int for_backward);
 
 /* Paper Eq. 3, forward (attention_forward of the appendix pseudocode).
@@ -125,7 +126,7 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
 /* Backward of Eq. 3 (attention_backward(dattn, q, k, v) -> dq, dk, dv): the scores are
  * recomputed from q, k; nothing saved by the forward is needed.  dout uses row_stride_o,
  * dq/dk/dv use the strides of q/k/v.  dq, dk, dv are deterministic: no atomics; partial sums
- * of cut key blocks are added in a fixed order.  With p->d_rab_table set the dQ pass also sums
+ * of cut blocks (key blocks of a global prefix; query blocks of a small batch) are added in a fixed order.  With p->d_rab_table set the dQ pass also sums
  * dS per distance with fp32 atomics (run-to-run differences at rounding level) and a small
  * kernel folds the distances into buckets. */
 int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, const void* dout,

@@ -18,9 +18,10 @@ inline int64_t max_items_for(const hstu_attn_params* p, int block_rows) {
 }
 
 struct Layout {           // byte offsets inside a workspace
-  size_t header[2], items[2], seq_base[2], bias, splits, partial, dbias, total;
+  size_t header[2], items[2], seq_base[2], bias, splits, partial, splits_dq, partial_dq, dbias, total;
   int max_items[2];
-  int slot_cap;           // partial-sum slots of the dK/dV pass (key blocks cut along the query axis)
+  int slot_cap;           // partial-sum slots of the dK/dV pass (key blocks cut along the query axis) or of the forward
+  int slot_cap_dq;        // ... of the dQ pass (query blocks of a small batch cut along the key axis)
 };
 
 // Slots for the pieces of cut key blocks: at most 768 (about 1.5 per workgroup slot of the chip), never more than
@@ -43,6 +44,9 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
     if ((for_backward && s == 1) || !for_backward) {
       l.slot_cap = slot_cap_for(l.max_items[s]);
       l.max_items[s] += l.slot_cap;
+    } else {
+      l.slot_cap_dq = slot_cap_for(l.max_items[s]);
+      l.max_items[s] += l.slot_cap_dq;
     }
     l.header[s] = off; off += kAlign;
     l.items[s] = off; off += align_up((size_t)l.max_items[s] * sizeof(WorkItem));
@@ -59,6 +63,9 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
     l.splits = off; off += align_up((size_t)(l.slot_cap / 2 + 1) * sizeof(SplitItem));
     l.partial = off;
     off += align_up((size_t)l.slot_cap * 2 * dkv_block_rows(p->dtype, p->head_dim) * p->head_dim * sizeof(float));
+    l.splits_dq = off; off += align_up((size_t)(l.slot_cap_dq / 2 + 1) * sizeof(SplitItem));
+    l.partial_dq = off;
+    off += align_up((size_t)l.slot_cap_dq * dq_block_rows(p->dtype, p->head_dim) * p->head_dim * sizeof(float));
     l.dbias = off;                                     // per-distance sums of dS for the bias-table gradient
     off += align_up((size_t)p->num_heads * ((size_t)p->max_seqlen + 1) * sizeof(float));
   }
@@ -270,7 +277,9 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
     SchedHeader* const hd[2] = {(SchedHeader*)(ws + l.header[0]), (SchedHeader*)(ws + l.header[1])};
     WorkItem* const it[2] = {(WorkItem*)(ws + l.items[0]), (WorkItem*)(ws + l.items[1])};
     int32_t* const sb[2] = {(int32_t*)(ws + l.seq_base[0]), (int32_t*)(ws + l.seq_base[1])};
-    if (launch_schedule_pair(a, rows, cols, hd, it, sb, (SplitItem*)(ws + l.splits), l.slot_cap, stream) != hipSuccess)
+    SplitItem* const sp[2] = {(SplitItem*)(ws + l.splits_dq), (SplitItem*)(ws + l.splits)};
+    const int caps[2] = {l.slot_cap_dq, l.slot_cap};
+    if (launch_schedule_pair(a, rows, cols, hd, it, sb, sp, caps, stream) != hipSuccess)
       return HSTU_ERR_LAUNCH;
   }
   if (p->d_rab_table) {
@@ -282,12 +291,13 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
     a.max_items = l.max_items[s];
     a.header = (const SchedHeader*)(ws + l.header[s]);
     a.items = (const WorkItem*)(ws + l.items[s]);
-    a.partial = (float*)(ws + l.partial);
-    a.splits = (const SplitItem*)(ws + l.splits);
+    a.partial = (float*)(ws + (s == 0 ? l.partial_dq : l.partial));
+    a.splits = (const SplitItem*)(ws + (s == 0 ? l.splits_dq : l.splits));
     {
-      ProfScope ps(s == 0 ? "attn_bwd_dq" : "attn_bwd_dkdv", stream);     // the dK/dV figure includes its combine kernel
+      ProfScope ps(s == 0 ? "attn_bwd_dq" : "attn_bwd_dkdv", stream);     // each figure includes its combine kernel
       const hipError_t e = s == 0 ? launch_attn_bwd_dq(a, p->dtype, stream) : launch_attn_bwd_dkdv(a, p->dtype, stream);
       if (e != hipSuccess) return HSTU_ERR_LAUNCH;
+      if (s == 0 && launch_dq_combine(a, p->dtype, l.slot_cap_dq / 2, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
       if (s == 1 && launch_dkdv_combine(a, p->dtype, l.slot_cap / 2, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
     }
     if (s == 0 && p->d_rab_table) {

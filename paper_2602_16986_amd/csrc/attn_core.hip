@@ -856,7 +856,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     if (ntiles > t_begin) dacc_flush((ntiles - 1 - t_begin) & 1, tr.at(ntiles - 1));
   }
   // ---- epilogue: scale once, convert, store.  Lane x holds features ob*32 + 8*(r/4) + 4*hf + r%4.
-  if constexpr (MODE == kBwdDKDV || MODE == kFwd) {
+  {
     if (item.slot >= 0) {
       // a piece of a cut block: raw fp32 sums go to its slot [outputs][block row][D]; the combine kernel finishes
       float* dst = a.partial + (((int64_t)item.slot * C::NOUT) * C::BX + (wave * 32 + l32)) * D;
@@ -899,18 +899,20 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
 }
 
 // Adds the partial sums of one cut block in piece order (fixed order: deterministic), applies the output scale and
-// writes the rows: dK and dV of a key block (FWD = false) or the attention output of a query block whose key axis was
-// cut (FWD = true: the forward over a query tail, few rows against long histories).
+// writes the rows: dK and dV of a key block cut along the query axis, or the attention output (forward) or dQ (dQ pass) of
+// a query block cut along the key axis (small batches; the forward over a query tail: few rows against long histories).
 // Grid: (possible cut blocks, 8); block (b, rb, h) rows split 8 ways.
-template <typename E, int D, bool FWD>
+enum { kCombineDKDV = 0, kCombineFwd = 1, kCombineDQ = 2 };
+template <typename E, int D, int WHAT>
 __global__ __launch_bounds__(256) void combine_kernel(const AttnArgs a, int block_rows) {
+  constexpr bool FWD = WHAT == kCombineFwd;
   const int si = blockIdx.x;
   if (si >= a.header->splits) return;
   const SplitItem it = a.splits[si];
   const int seq0 = a.offsets[it.b], L = a.offsets[it.b + 1] - seq0;
   const int xb = it.rb_h >> 8, h = it.rb_h & 255;
   constexpr int VPR = D / 4;                                           // float4 per row
-  constexpr int NOUT = FWD ? 1 : 2;
+  constexpr int NOUT = WHAT == kCombineDKDV ? 2 : 1;
   int q0 = 0;
   if (FWD && a.query_tail > 0) q0 = max(L - (a.num_targets ? a.num_targets[it.b] : 0) - a.query_tail, 0);
   const int rows_here = block_rows / 8;
@@ -921,10 +923,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttnArgs a, int bloc
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int pc = 0; pc < it.pieces; ++pc)
       acc += *(const f32x4*)(a.partial + ((((int64_t)(it.first_slot + pc) * NOUT + o) * block_rows + r) * D) + 4 * c4);
-    const float scale = (!FWD && o == 0) ? a.inv_n * a.alpha : a.inv_n * kLn2;
+    const float scale = (!FWD && o == 0) ? a.inv_n * a.alpha : a.inv_n * kLn2;      // dQ and dK owe alpha, the forward and dV ln 2
     acc *= scale;
-    E* base = FWD ? (E*)a.out : (E*)(o == 0 ? a.dk : a.dv);
-    const int64_t stride = FWD ? a.so : (o == 0 ? a.sk : a.sv);
+    E* base = FWD ? (E*)a.out : (WHAT == kCombineDQ ? (E*)a.dq : (E*)(o == 0 ? a.dk : a.dv));
+    const int64_t stride = FWD ? a.so : (WHAT == kCombineDQ ? a.sq : (o == 0 ? a.sk : a.sv));
     E* dst = base + (int64_t)(seq0 + x) * stride + (int64_t)h * D + 4 * c4;
     if constexpr (sizeof(E) == 2) *(u32x2*)dst = (u32x2){pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
     else *(f32x4*)dst = acc;
@@ -1030,7 +1032,7 @@ hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream
   return dispatch<kBwdDKDV, kDkvWavesBf16, kDkvWavesFp32>(a, dtype, stream);
 }
 
-template <bool FWD>
+template <int FWD>
 static hipError_t launch_combine(const AttnArgs& a, int dtype, int rows, int max_splits, hipStream_t stream) {
   if (max_splits <= 0) return hipSuccess;
   const dim3 grid(max_splits, 8), block(256);
@@ -1053,11 +1055,15 @@ static hipError_t launch_combine(const AttnArgs& a, int dtype, int rows, int max
 }
 
 hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream) {
-  return launch_combine<false>(a, dtype, dkv_block_rows(dtype, a.D), max_splits, stream);
+  return launch_combine<kCombineDKDV>(a, dtype, dkv_block_rows(dtype, a.D), max_splits, stream);
 }
 
 hipError_t launch_fwd_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream) {
-  return launch_combine<true>(a, dtype, fwd_block_rows(dtype, a.D), max_splits, stream);
+  return launch_combine<kCombineFwd>(a, dtype, fwd_block_rows(dtype, a.D), max_splits, stream);
+}
+
+hipError_t launch_dq_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream) {
+  return launch_combine<kCombineDQ>(a, dtype, dq_block_rows(dtype, a.D), max_splits, stream);
 }
 
 }  // namespace hstu

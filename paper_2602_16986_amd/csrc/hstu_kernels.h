@@ -57,8 +57,8 @@ hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, boo
 // The two lists of the backward pass in one launch: [0] query blocks (dQ pass), [1] key blocks (dK/dV pass).
 // `splits` / `slot_cap`: list of cut key blocks and number of partial-sum slots available to the dK/dV list.
 hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
-                                WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* splits, int slot_cap,
-                                hipStream_t stream);
+                                WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* const splits[2],
+                                const int slot_cap[2], hipStream_t stream);
 hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
                               hipStream_t stream);
 
@@ -80,6 +80,7 @@ hipError_t launch_dbias_reduce(const float* dist, const int32_t* bounds, int num
 hipError_t launch_dkdv_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream);
 // the same for query blocks of the forward whose key axis was cut (forward over a query tail): writes the output rows
 hipError_t launch_fwd_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream);
+hipError_t launch_dq_combine(const AttnArgs& a, int dtype, int max_splits, hipStream_t stream);
 
 // gated_norm.hip
 // Row-wise layer norm with weight (and optional bias), optionally gated by U; row strides in elements.

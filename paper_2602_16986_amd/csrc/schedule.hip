@@ -24,6 +24,7 @@ constexpr int kItemsPerThread = kSortMax / kSchedThreads;
 constexpr int kMinChunk = 8;         // a long key block is cut into pieces of at least this many tiles ...
 constexpr int kTargetChunks = 2048;  // ... and of about 1/2048 of all scheduled tiles (4 per workgroup slot of the chip)
 constexpr int kFwdTargetChunks = 1536;   // forward lists: 2 x chunk = one slot's share when 768 workgroups are resident
+constexpr int kDqTargetChunks = 1024;    // dQ lists: the same with 512 resident workgroups
 
 // One workgroup builds one list; the backward pass launches two (dQ blocks and dK/dV blocks) side by side.
 struct SchedJob {
@@ -315,10 +316,11 @@ hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, boo
 }
 
 hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
-                                WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* splits, int slot_cap,
-                                hipStream_t stream) {
-  const SchedJob j0 = {block_rows[0], tile_cols[0], 0, 0, 0, 0, kTargetChunks, header[0], items[0], seq_base[0], nullptr};
-  const SchedJob j1 = {block_rows[1], tile_cols[1], 1, 0, slot_cap, 0, kTargetChunks, header[1], items[1], seq_base[1], splits};
+                                WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* const splits[2],
+                                const int slot_cap[2], hipStream_t stream) {
+  // dQ list (query-major): equal pieces of about one slot's share, 512 slots at two workgroups per compute unit
+  const SchedJob j0 = {block_rows[0], tile_cols[0], 0, 0, slot_cap[0], 1, kDqTargetChunks, header[0], items[0], seq_base[0], splits[0]};
+  const SchedJob j1 = {block_rows[1], tile_cols[1], 1, 0, slot_cap[1], 0, kTargetChunks, header[1], items[1], seq_base[1], splits[1]};
   hipLaunchKernelGGL(schedule_kernel, dim3(2), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
                      a.K2, j0, j1);
   return hipGetLastError();

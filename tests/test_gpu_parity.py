@@ -370,3 +370,20 @@ def test_reuse_schedule_gives_identical_results(hb):
         hb.hstu_attn_fwd(dw.problem, dw.q, dw.k, dw.v, dw.out, dw.ws_fwd)
     assert e.value.status == -2
     dw.problem.params.reuse_schedule = 0
+
+
+@pytest.mark.parametrize("lengths,H,K1,K2", [([3000], 2, -1, 0), ([1500, 40], 1, -1, 0), ([2500], 2, 700, 300)])
+def test_small_batch_blocks_are_cut_in_every_pass(hb, lengths, H, K1, K2):
+    """One or two long sequences: fewer blocks than the chip has workgroup slots, so the forward and the dQ pass cut their
+    query blocks along the key axis and the dK/dV pass its key blocks along the query axis (partial sums + combine); parity
+    as for any other case, and the lists do hold pieces."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.build("small-batch", lengths, H, 128, "bf16", seed=5, K1=K1, K2=K2, backward=True)
+    run_case(w)
+    dw = DeviceWorkload(w)
+    dw.attn_fwd()
+    dw.attn_bwd()
+    torch.cuda.synchronize()
+    blocks = sum((L + 127) // 128 for L in lengths) * H
+    assert hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)["items"] > blocks
+    assert hb.hstu_attn_schedule_stats(dw.problem, dw.ws_bwd, True)["items"] > blocks      # the dQ list
