@@ -1006,7 +1006,7 @@ __global__ __launch_bounds__(256) void dbias_reduce_kernel(const float* __restri
   red[threadIdx.x] = acc;
   __syncthreads();
   for (int off = 128; off > 0; off >>= 1) {
-    if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
     __syncthreads();
   }
   if (threadIdx.x == 0) dtable[(size_t)h * nb + c] = red[0] * scale;

@@ -79,8 +79,8 @@ int make_plan(Plan& pl, const void* A, const void* B, const void* C, void* D, vo
       if (!ok || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) continue;
       if (!have || ms < best_ms) { have = true; best_ms = ms; best = i; }
     }
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
     if (!have) return -2;
   }
   pl.algo = res[best].algo;

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   const SchedJob job = blockIdx.x == 0 ? job0 : job1;
   const int block_rows = job.block_rows, tile_cols = job.tile_cols, key_major = job.key_major, tail = job.query_tail;
   // first block of a sequence that holds a query row to compute
-  auto first_block = [&](int L, int hist) { return tail > 0 ? max(hist - tail, 0) / block_rows : 0; };
+  auto first_block = [&](int hist) { return tail > 0 ? max(hist - tail, 0) / block_rows : 0; };
   SchedHeader* header = job.header;
   WorkItem* items = job.items;
   int32_t* seq_base = job.seq_base;
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     if (b < B) {
       const int L = offsets[b + 1] - offsets[b];
       nb = (L + block_rows - 1) / block_rows;
-      if (tail > 0 && nb > 0) nb -= first_block(L, L - (num_targets ? num_targets[b] : 0));
+      if (tail > 0 && nb > 0) nb -= first_block(L - (num_targets ? num_targets[b] : 0));
     }
     scan[tid] = nb;
     __syncthreads();
