@@ -117,8 +117,9 @@ AttnArgs make_args(const hstu_attn_params* p, const void* q, const void* k, cons
   a.sq = p->row_stride_q; a.sk = p->row_stride_k; a.sv = p->row_stride_v; a.so = p->row_stride_o;
   a.offsets = p->seq_offsets; a.num_targets = p->num_targets;
   a.B = p->batch; a.H = p->num_heads; a.D = p->head_dim; a.T = p->total_tokens; a.max_seqlen = p->max_seqlen;
-  a.K1 = p->local_window < 0 ? -1 : p->local_window;
-  a.K2 = p->global_prefix;
+  // sequences are shorter than 2^24 tokens: windows beyond 2^28 mean the same and keep the kernels' index sums inside int32
+  a.K1 = p->local_window < 0 ? -1 : (p->local_window < (1 << 28) ? p->local_window : (1 << 28));
+  a.K2 = p->global_prefix < (1 << 28) ? p->global_prefix : (1 << 28);
   a.alpha = p->alpha; a.inv_n = p->inv_n;
   a.query_tail = p->query_tail > 0 ? p->query_tail : 0;
   return a;

@@ -387,3 +387,22 @@ def test_small_batch_blocks_are_cut_in_every_pass(hb, lengths, H, K1, K2):
     blocks = sum((L + 127) // 128 for L in lengths) * H
     assert hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)["items"] > blocks
     assert hb.hstu_attn_schedule_stats(dw.problem, dw.ws_bwd, True)["items"] > blocks      # the dQ list
+
+
+def test_huge_window_and_prefix_equal_dense(hb):
+    """local_window / global_prefix near INT32_MAX (the index sums of the kernels must not wrap): same results, bit for bit,
+    as the dense causal mask, forward and backward, with a ragged last tile and candidates."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    lengths = [333, 97, 1000]
+    targets = np.array([5, 0, 40], dtype=np.int32)
+    outs = []
+    for K1, K2 in ((-1, 0), (2 ** 31 - 1, 0), (2 ** 31 - 1, 2 ** 31 - 1), (0, 2 ** 31 - 1)):
+        w = wl.build("huge-window", lengths, 2, 128, "bf16", seed=9, K1=K1, K2=K2, num_targets=targets, backward=True)
+        dw = DeviceWorkload(w)
+        dw.attn_fwd()
+        dw.attn_bwd()
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (dw.out, dw.dq, dw.dk, dw.dv)])
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
