@@ -145,7 +145,7 @@ __device__ __forceinline__ void diag_all(std::integer_sequence<int, R...>, const
 template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false, bool CAND = false>
 __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) void attn_kernel(const AttnArgs a) {
   static_assert(!DBIAS || MODE == kBwdDQ, "the bias gradient rides with the dQ pass");
-  static_assert(!CAND || MODE != kBwdDKDV, "candidate fast paths: query-stationary passes");
+  constexpr bool CANDQ = CAND && MODE != kBwdDKDV, CANDK = CAND && MODE == kBwdDKDV;
   using C = Cfg<E, D, MODE, NWAVES>;
   using RFrag = typename ResidentFrag<E>::type;
   // 256-byte alignment: the fragment reads below form LDS addresses as integers, base included, and XOR the swizzle in
@@ -238,8 +238,8 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   // this lane's start inside the bias strip: copy c = s0 mod 4 makes its 4-entry reads 16-byte aligned
   // Query-stationary passes: a candidate row (x >= n) stands at position n for the mask and for the bias, so the strip is
   // addressed with the row's effective position px, and a block made of candidates only puts the strip's origin at n.
-  const int x0v = CAND ? min(x0, g.n) : x0;
-  const int strip_s0 = C::BX - 1 - ((CAND ? min(x, g.n) : x) - x0v) + 4 * hf;
+  const int x0v = CANDQ ? min(x0, g.n) : x0;
+  const int strip_s0 = C::BX - 1 - ((CANDQ ? min(x, g.n) : x) - x0v) + 4 * hf;
   const int strip_lane = (strip_s0 & 3) * C::SLEN + (strip_s0 & ~3);
 
   // ---- staging of the streamed tiles: global -> LDS directly, or through registers
@@ -312,7 +312,9 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     nx_a1 = (uint64_t)(uintptr_t)Y1 + (uint64_t)(uint32_t)yrow * rowb1;
     nx_a2 = (uint64_t)(uintptr_t)Y2 + (uint64_t)(uint32_t)yrow * rowb2;
     nx_left = valid ? L - yrow : 0;
-    nx_d0x4 = 4 * ((MODE == kBwdDKDV) ? yt * C::BN - x0 - (C::BX - 1) : x0v + (C::BX - 1) - yt * C::BN);
+    // (dK/dV pass, CANDK: a tile of candidate queries stands at position n as a whole: its strip starts there, and entry
+    // BX - 1 - (key - x0) of it is the bias of that key against every candidate)
+    nx_d0x4 = 4 * ((MODE == kBwdDKDV) ? (CANDK ? min(yt * C::BN, g.n) : yt * C::BN) - x0 - (C::BX - 1) : x0v + (C::BX - 1) - yt * C::BN);
     nx_bias_bytes = valid ? (uint32_t)a.bias_stride * 4u : 0u;
   };
   const uint64_t bias_addr = (uint64_t)(uintptr_t)bias_h;
@@ -441,8 +443,8 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     // Fully visible tiles of candidate rows (all at position n) against history keys are recognised in the query-stationary
     // passes only (the dK/dV pass has no strip by the distance n - key), and not with the bias gradient, which adds the dS of
     // candidate rows to the table by that distance one by one: those take the masked path.
-    int kind = (MODE == kBwdDKDV) ? classify_tile(g, y0, y0 + C::BN - 1, xw0, xw0 + 31, false)
-                                  : classify_tile(g, xw0, xw0 + 31, y0, y0 + C::BN - 1, CAND && !DBIAS);
+    int kind = (MODE == kBwdDKDV) ? classify_tile(g, y0, y0 + C::BN - 1, xw0, xw0 + 31, CANDK)
+                                  : classify_tile(g, xw0, xw0 + 31, y0, y0 + C::BN - 1, CANDQ && !DBIAS);
     if (xw0 >= L || xw0 + 31 < q0) kind = kTileEmpty;
 
     // The next tile's global loads are issued piecewise between the score products: the compute unit's
@@ -589,8 +591,17 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
         // In the query-stationary passes candidate rows against history keys work the same way with the rows' effective
         // position n.  (In the dK/dV pass a strip by the distance n - key would be needed: those tiles stay on the general path.)
         const bool tile_hist = min(y0 + C::BN, L) - 1 < g.n;                 // the streamed rows are all history
-        const bool seeded = kind == kTilePartial && (MODE == kBwdDKDV ? tile_hist : (stat_hist || (CAND && tile_hist)));
-        if ((kind == kTileFull || seeded) && bias_h) {
+        // dK/dV pass with candidates: a tile of candidate queries against a wave of history keys
+        const bool cand_tile = CANDK && y0 >= g.n && stat_hist;
+        const bool seeded = kind == kTilePartial && (MODE == kBwdDKDV ? (tile_hist || cand_tile) : (stat_hist || (CANDQ && tile_hist)));
+        if (CANDK && cand_tile && (kind == kTileFull || seeded) && bias_h) {
+          // entry BX - 1 - (x - x0) of the strip anchored at n (strip_lane also carries this lane's 4 hf register offset)
+          const float bias_c = *((const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane - 4 * hf);
+#pragma unroll
+          for (int u = 0; u < SBG; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc1[u][r] = bias_c;
+        } else if ((kind == kTileFull || seeded) && bias_h) {
           // the distance of every pair that counts is >= 0: seed the accumulators with the bias strip
           const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
 #pragma unroll
@@ -694,7 +705,15 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
               c2[u][r] = vis ? p : 0.f;
             }
           };
-          if (seeded && MODE == kBwdDKDV) {
+          if (CANDK && seeded && cand_tile) {
+            // candidate queries (all at position n) against history keys: one yes/no per key, and the rows past the end
+            const bool key_vis = x_ok && (g.K1 < 0 || g.n - x < g.K1 || x < g.K2);
+            const int up = key_vis ? L - 1 - y0 - 4 * hf : -1;
+#pragma unroll
+            for (int u = 0; u < SBG; ++u)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) mixed(u, r, sc1[u][r], (sg + u) * 32 + 8 * (r >> 2) + (r & 3) <= up);
+          } else if (seeded && MODE == kBwdDKDV) {
             // History rows only, seen from key x: the queries y >= x with y - x < K1 (any y >= x for a key of the global
             // prefix or a dense mask), and y < L.  Query = y0 + c + 4 hf, c a compile-time constant per register.
             const int lo = (x_ok ? x - y0 : (1 << 30)) - 4 * hf;                              // c >= lo  <=>  y >= x
@@ -727,7 +746,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
             // to this lane's register pattern (key = y0 + c + 4 hf, c a compile-time constant per register) these are three
             // per-lane bounds, and the ones that cannot bind anywhere in this wave's 32 x BN pairs are dropped for the tile.
             // (a candidate row stands at px = n; then the tile holds history keys only and the first bound never binds)
-            const int px = CAND ? min(x, g.n) : x;
+            const int px = CANDQ ? min(x, g.n) : x;
             const int up = (x_ok ? px - y0 : -1) - 4 * hf;               // c <= up   <=>  y <= x (no key for a row past the end)
             const int lo = px - g.K1 + 1 - y0 - 4 * hf;                   // c >= lo   <=>  x - y < K1
             const int pre = g.K2 - y0 - 4 * hf;                           // c <  pre  <=>  y < K2
@@ -1029,6 +1048,7 @@ hipError_t launch_dbias_reduce(const float* dist, const int32_t* bounds, int num
   return hipGetLastError();
 }
 hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream) {
+  if (a.num_targets) return dispatch<kBwdDKDV, kDkvWavesBf16, kDkvWavesFp32, false, true>(a, dtype, stream);
   return dispatch<kBwdDKDV, kDkvWavesBf16, kDkvWavesFp32>(a, dtype, stream);
 }
 
