@@ -138,8 +138,7 @@ __device__ __forceinline__ void diag_all(std::integer_sequence<int, R...>, const
 
 // DBIAS (dQ pass only): also sum dS along the diagonals of every tile (pairs of equal distance i - j) into
 // a.dbias_dist[h, distance]; dbias_reduce_kernel folds distances into buckets afterwards.
-// CAND (query-stationary passes, batches with candidate rows): the fast paths also cover candidate rows against history
-// keys.  A candidate row stands at position n for the mask and for the bias, so full and mask-edge tiles of such rows work
+// CAND (batches with candidate rows): the fast paths also cover candidate rows against history keys.  A candidate row stands at position n for the mask and for the bias, so full and mask-edge tiles of such rows work
 // like those of history rows once the bias strip is addressed with the row's effective position.  Batches without
 // candidates run the instantiation without it (a few scalar instructions per tile less).
 template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false, bool CAND = false>
@@ -440,9 +439,9 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
 
     // How this wave's 32 stationary rows relate to the tile: nothing visible (skip), everything
     // visible (no mask arithmetic, bias from the strip), or mixed (generic per-element path).
-    // Fully visible tiles of candidate rows (all at position n) against history keys are recognised in the query-stationary
-    // passes only (the dK/dV pass has no strip by the distance n - key), and not with the bias gradient, which adds the dS of
-    // candidate rows to the table by that distance one by one: those take the masked path.
+    // Fully visible tiles of candidate rows (all at position n) against history keys are recognised in the instantiations
+    // for batches with candidates, but not with the bias gradient, which adds the dS of candidate rows to the table by the
+    // distance n - j one by one: those take the masked path.
     int kind = (MODE == kBwdDKDV) ? classify_tile(g, y0, y0 + C::BN - 1, xw0, xw0 + 31, CANDK)
                                   : classify_tile(g, xw0, xw0 + 31, y0, y0 + C::BN - 1, CANDQ && !DBIAS);
     if (xw0 >= L || xw0 + 31 < q0) kind = kTileEmpty;
@@ -589,7 +588,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
         // per element (no table gathers, whose wait would also wait for the tile being fetched).
         // In the dK/dV pass the query rows are the streamed tile's.
         // In the query-stationary passes candidate rows against history keys work the same way with the rows' effective
-        // position n.  (In the dK/dV pass a strip by the distance n - key would be needed: those tiles stay on the general path.)
+        // position n; in the dK/dV pass a tile of candidate queries has its strip anchored at n (see set_next).
         const bool tile_hist = min(y0 + C::BN, L) - 1 < g.n;                 // the streamed rows are all history
         // dK/dV pass with candidates: a tile of candidate queries against a wave of history keys
         const bool cand_tile = CANDK && y0 >= g.n && stat_hist;
