@@ -138,9 +138,11 @@ __device__ __forceinline__ void diag_all(std::integer_sequence<int, R...>, const
 
 // DBIAS (dQ pass only): also sum dS along the diagonals of every tile (pairs of equal distance i - j) into
 // a.dbias_dist[h, distance]; dbias_reduce_kernel folds distances into buckets afterwards.
-// CAND (batches with candidate rows): the fast paths also cover candidate rows against history keys.  A candidate row stands at position n for the mask and for the bias, so full and mask-edge tiles of such rows work
-// like those of history rows once the bias strip is addressed with the row's effective position.  Batches without
-// candidates run the instantiation without it (a few scalar instructions per tile less).
+// CAND (batches with candidate rows): the fast paths also cover candidate rows against history keys.  A candidate row
+// stands at position n for the mask and for the bias, so full and mask-edge tiles of such rows work like those of history
+// rows once the bias strip is addressed with the row's effective position (query-stationary passes) or anchored at n
+// for a tile of candidate queries (dK/dV pass).  Batches without candidates run the instantiation without it (a few
+// scalar instructions per tile less).
 template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false, bool CAND = false>
 __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) void attn_kernel(const AttnArgs a) {
   static_assert(!DBIAS || MODE == kBwdDQ, "the bias gradient rides with the dQ pass");
