@@ -265,7 +265,11 @@ const char* hstu_status_string(int status);
 /* Statistics of the last tile schedule written by hstu_attn_fwd/bwd into `workspace`
  * (valid after the stream has been synchronised): HOST out[0] = scheduled row blocks x heads,
  * out[1] = scheduled (row block, column block) tiles x heads, out[2] = tiles a dense L x L
- * grid would have.  Reads device memory with a blocking copy; for reporting only. */
+ * grid would have.  Reads device memory with a blocking copy; for reporting only.
+ * Returns HSTU_ERR_SHAPE (out[0] = 0) when the scheduler of that call found the DEVICE copies of seq_offsets / num_targets
+ * inconsistent with the description (offsets not starting at 0, decreasing, a sequence longer than max_seqlen, an end past
+ * total_tokens, a candidate count outside [0, L]): such a call computes nothing and leaves every output untouched, instead of
+ * addressing rows outside the tensors (the host cannot see device-side offsets when seq_offsets_host is NULL). */
 int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, int for_backward, int64_t out[3]);
 
 /* Per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every kernel

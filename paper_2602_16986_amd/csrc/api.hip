@@ -320,7 +320,7 @@ int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, i
   if (hipMemcpy(&h, (const unsigned char*)workspace + l.header[0], sizeof(h), hipMemcpyDeviceToHost) != hipSuccess)
     return HSTU_ERR_LAUNCH;
   out[0] = h.count; out[1] = h.tiles; out[2] = h.dense_tiles;
-  return HSTU_OK;
+  return h.bad_batch ? HSTU_ERR_SHAPE : HSTU_OK;          // the scheduler found the device-side offsets inconsistent
 }
 
 static int validate_norm(int64_t T, int32_t D, int32_t dtype) {

@@ -12,7 +12,8 @@ struct SchedHeader {
   int64_t tiles;          // scheduled (row block, column block) tiles, all heads
   int64_t dense_tiles;    // tiles of the full L x L grids, all heads
   int32_t chunk_tiles;    // piece size used for the cut blocks
-  int32_t pad;
+  int32_t bad_batch;      // 1: seq_offsets / num_targets on the device contradict the description (then count = 0: no kernel
+                          // touches a token row)
 };
 
 struct WorkItem {

@@ -59,7 +59,8 @@ __device__ unsigned long long block_scan64(unsigned long long v, unsigned long l
 
 __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* __restrict__ offsets,
                                                                  const int32_t* __restrict__ num_targets, int B, int H,
-                                                                 int K1, int K2, SchedJob job0, SchedJob job1) {
+                                                                 int K1, int K2, int T, int max_seqlen, SchedJob job0,
+                                                                 SchedJob job1) {
   const SchedJob job = blockIdx.x == 0 ? job0 : job1;
   const int block_rows = job.block_rows, tile_cols = job.tile_cols, key_major = job.key_major, tail = job.query_tail;
   // first block of a sequence that holds a query row to compute
@@ -79,6 +80,22 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   const int tid = threadIdx.x;
   if (tid == 0) { carry_s = 0; tiles_s = 0; dense_s = 0; }
   __syncthreads();
+
+  // 0. The offsets live on the device and the host may never have seen them: a batch whose offsets are not a non-decreasing
+  // walk from 0 to at most T in steps of at most max_seqlen, or whose candidate counts leave [0, L], gets an empty list
+  // (every kernel that follows then returns at once) instead of rows addressed outside the tensors.
+  {
+    int bad = 0;
+    for (int b = tid; b < B; b += kSchedThreads) {
+      const int o0 = offsets[b], o1 = offsets[b + 1];
+      const int m = num_targets ? num_targets[b] : 0;
+      bad |= (o0 < 0) | (o1 < o0) | (o1 - o0 > max_seqlen) | (o1 > T) | (m < 0) | (m > o1 - o0) | (b == 0 && o0 != 0);
+    }
+    if (__syncthreads_or(bad)) {
+      if (tid == 0) *job.header = SchedHeader{0, 0, 0, 0, 0, 1};
+      return;
+    }
+  }
 
   // 1. exclusive scan of blocks-per-sequence -> seq_base[b] (per head)
   for (int c0 = 0; c0 < B; c0 += kSchedThreads) {
@@ -311,7 +328,7 @@ hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, boo
   const SchedJob job = {block_rows, tile_cols, key_major ? 1 : 0, key_major ? 0 : a.query_tail, splits ? slot_cap : 0, even ? 1 : 0,
                         even ? kFwdTargetChunks : kTargetChunks, header, items, seq_base, splits};
   hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
-                     a.K2, job, job);
+                     a.K2, a.T, a.max_seqlen, job, job);
   return hipGetLastError();
 }
 
@@ -322,7 +339,7 @@ hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], cons
   const SchedJob j0 = {block_rows[0], tile_cols[0], 0, 0, slot_cap[0], 1, kDqTargetChunks, header[0], items[0], seq_base[0], splits[0]};
   const SchedJob j1 = {block_rows[1], tile_cols[1], 1, 0, slot_cap[1], 0, kTargetChunks, header[1], items[1], seq_base[1], splits[1]};
   hipLaunchKernelGGL(schedule_kernel, dim3(2), dim3(kSchedThreads), 0, stream, a.offsets, a.num_targets, a.B, a.H, a.K1,
-                     a.K2, j0, j1);
+                     a.K2, a.T, a.max_seqlen, j0, j1);
   return hipGetLastError();
 }
 

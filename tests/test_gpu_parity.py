@@ -406,3 +406,37 @@ def test_huge_window_and_prefix_equal_dense(hb):
     for other in outs[1:]:
         for a, b in zip(outs[0], other):
             assert torch.equal(a, b)
+
+
+def test_inconsistent_device_offsets_compute_nothing(hb):
+    """Offsets that live on the device only (no host copy to validate) and contradict the description: the scheduler writes an
+    empty work list, no output row is touched, and the statistics call reports the batch; a consistent batch in the same
+    workspace afterwards works as usual."""
+    from paper_2602_16986_amd.runner import DeviceWorkload
+    w = wl.small("bf16-targets")
+    dw = DeviceWorkload(w)
+    good = dw.offsets.clone()
+    cases = []
+    bad = good.clone(); bad[2] = bad[1] - 3; cases.append(("decreasing", bad, None))
+    bad = good.clone(); bad[-1] = w.T + 5; cases.append(("past the end", bad, None))
+    bad = good.clone(); bad[0] = 1; cases.append(("not from zero", bad, None))
+    tg = dw.num_targets.clone(); tg[0] = 10 ** 6; cases.append(("candidates > length", good.clone(), tg))
+    for what, off, targets in cases:
+        prob = hb.AttnProblem(dw.q, dw.k, dw.v, dw.out, off, max_seqlen=w.max_seqlen, num_targets=dw.num_targets if targets is None else targets,
+                              local_window=w.K1, global_prefix=w.K2, alpha=w.alpha, inv_n=1.0 / w.N, rab_table=dw.table,
+                              rab_bounds=dw.bounds)
+        dw.out.fill_(3.0)
+        dq, dk, dv = (torch.full_like(dw.q, 5.0) for _ in range(3))
+        hb.hstu_attn_fwd(prob, dw.q, dw.k, dw.v, dw.out, dw.ws_fwd)
+        hb.hstu_attn_bwd(prob, dw.q, dw.k, dw.v, dw.dout, dq, dk, dv, dw.ws_bwd)
+        torch.cuda.synchronize()
+        assert torch.all(dw.out == 3.0) and all(torch.all(t == 5.0) for t in (dq, dk, dv)), what
+        for ws, bwd in ((dw.ws_fwd, False), (dw.ws_bwd, True)):
+            with pytest.raises(hb.HstuError) as e:
+                hb.hstu_attn_schedule_stats(prob, ws, bwd)
+            assert e.value.status == -2, what
+    dw.attn_fwd()
+    torch.cuda.synchronize()
+    assert hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)["items"] > 0
+    ref = orc.attn_fwd(w.q, w.k, w.v, w.offsets, **oracle_args(w))
+    check("A after a rejected batch", to_np(dw.out), ref, TOL[w.dtype])
