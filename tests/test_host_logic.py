@@ -103,3 +103,13 @@ def test_workspace_query_rejects_descriptions_the_kernels_cannot_address():
     assert ws(max_seqlen=1 << 20, row_stride_v=4096) == 0    # 2^20 rows x 8 KiB >= 4 GiB
     assert ws(row_stride_q=4 * 128 + 4) == 0                 # rows must start on 16-byte boundaries
     assert ws(head_dim=96) == 0
+
+
+def test_public_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (and as C++) on its own, with no HIP or torch types."""
+    import subprocess
+    src = tmp_path / "abi.c"
+    src.write_text('#include "hstu_attn.h"\nint main(void) { hstu_attn_params p; hstu_layer_params q; (void)p; (void)q; return 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)], check=True)
