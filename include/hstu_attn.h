@@ -148,6 +148,21 @@ int hstu_gated_norm_bwd(int64_t T, int32_t D, int32_t dtype, const void* dy, con
                         const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
                         float* dbeta, void* workspace, size_t workspace_bytes, void* stream);
 
+/* hstu_gated_norm_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * hstu_gated_norm_bwd without the workspace: the partial column sums go to a device array that the library itself
+ * holds (hstu_gated_norm_bwd_static_max_bytes() = 16 MiB on every GPU the library runs on, until the process ends).
+ * A problem whose hstu_gated_norm_bwd_workspace_bytes(T, D) exceeds that size is rejected with HSTU_ERR_WORKSPACE and
+ * nothing is launched (no supported D reaches it today).  The call allocates and frees nothing and does not
+ * synchronise; the first call on a device looks up the array's address on that device (no allocation either; make
+ * that first call outside a graph capture).  All calls on one GPU share the array: calls that may overlap on one GPU
+ * (different streams, different host threads) race on it and must be serialised by the caller; calls on one stream
+ * are safe.  Nothing has to be cleared between calls: every launch overwrites all it reads. */
+size_t hstu_gated_norm_bwd_static_max_bytes(void);
+int hstu_gated_norm_bwd_static(int64_t T, int32_t D, int32_t dtype, const void* dy, const void* attn, const void* u,
+                               const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
+                               float* dbeta, void* stream);
+
 /*
  * Attention truncation (paper Section 4.3, "Attention Truncation"): after a first group of layers has seen
  * the whole sequence, the remaining layers run on a segment of it, and the segment the paper settles on is

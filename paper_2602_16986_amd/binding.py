@@ -73,6 +73,10 @@ def _load() -> ctypes.CDLL:
     lib.hstu_gated_norm_bwd_workspace_bytes.argtypes = [i64, i32]
     lib.hstu_gated_norm_bwd.restype = ctypes.c_int
     lib.hstu_gated_norm_bwd.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.hstu_gated_norm_bwd_static_max_bytes.restype = sz
+    lib.hstu_gated_norm_bwd_static_max_bytes.argtypes = []
+    lib.hstu_gated_norm_bwd_static.restype = ctypes.c_int
+    lib.hstu_gated_norm_bwd_static.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
     lib.hstu_truncate_offsets.restype = ctypes.c_int
     lib.hstu_truncate_offsets.argtypes = [i32, i32, vp, vp, vp, vp]
     lib.hstu_truncate_fwd.restype = ctypes.c_int
@@ -100,6 +104,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ["hstu_attn_workspace_bytes", "hstu_attn_fwd", "hstu_attn_bwd", "hstu_gated_norm_fwd",
            "hstu_gated_norm_bwd_workspace_bytes", "hstu_gated_norm_bwd", "hstu_status_string",
+           "hstu_gated_norm_bwd_static_max_bytes", "hstu_gated_norm_bwd_static",
            "hstu_attn_schedule_stats", "hstu_profile_enable", "hstu_profile_read",
            "hstu_truncate_offsets", "hstu_truncate_fwd", "hstu_truncate_bwd",
            "hstu_layer_workspace_bytes", "hstu_layer_fwd", "hstu_layer_bwd",
@@ -211,6 +216,19 @@ def hstu_gated_norm_bwd(dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta,
                                   workspace.numel(), _stream(stream))
     if st != HSTU_OK:
         raise HstuError(st, "hstu_gated_norm_bwd")
+
+
+def hstu_gated_norm_bwd_static_max_bytes() -> int:
+    return int(_lib.hstu_gated_norm_bwd_static_max_bytes())
+
+
+def hstu_gated_norm_bwd_static(dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta, stream=None) -> None:
+    T = attn.shape[0]
+    D = attn.numel() // T if T else int(np.prod(attn.shape[1:]))
+    st = _lib.hstu_gated_norm_bwd_static(T, D, _dtype_code(attn), _ptr(dy), _ptr(attn), _ptr(u), _ptr(gamma), _ptr(beta),
+                                         float(eps), _ptr(dattn), _ptr(du), _ptr(dgamma), _ptr(dbeta), _stream(stream))
+    if st != HSTU_OK:
+        raise HstuError(st, "hstu_gated_norm_bwd_static")
 
 
 def _row_geometry(t: torch.Tensor):

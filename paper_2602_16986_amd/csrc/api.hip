@@ -5,6 +5,8 @@
 #include "hstu_kernels.h"
 #include "profile.h"
 
+#include <mutex>
+
 using namespace hstu;
 
 namespace {
@@ -363,6 +365,53 @@ int hstu_gated_norm_bwd(int64_t T, int32_t D, int32_t dtype, const void* dy, con
     return HSTU_ERR_WORKSPACE;
   ProfScope ps("gated_norm_bwd", (hipStream_t)stream);
   if (launch_gated_norm_bwd(T, D, dtype, dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta, (float*)workspace,
+                            (hipStream_t)stream) != hipSuccess)
+    return HSTU_ERR_LAUNCH;
+  return HSTU_OK;
+}
+
+// ---- the gated-norm backward for callers that cannot allocate -------------------------------------------------
+// Same kernels as hstu_gated_norm_bwd; the partial column sums live in a file-scope device array instead of a
+// caller-provided workspace.  In host code the array's name is only a stand-in: the address the kernels get is the one
+// hipGetSymbolAddress reports for the current device (every GPU holds its own copy), looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxScratchDevices = 64;
+static void* g_scratch_ptr[kMaxScratchDevices];
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) return HSTU_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return HSTU_ERR_LAUNCH;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return HSTU_OK;
+}
+
+size_t hstu_gated_norm_bwd_static_max_bytes(void) { return kStaticScratchBytes; }
+
+int hstu_gated_norm_bwd_static(int64_t T, int32_t D, int32_t dtype, const void* dy, const void* attn, const void* u,
+                               const float* gamma, const float* beta, float eps, void* dattn, void* du, float* dgamma,
+                               float* dbeta, void* stream) {
+  const int st = validate_norm(T, D, dtype);
+  if (st != HSTU_OK) return st;
+  if (!gamma || !dgamma) return HSTU_ERR_NULL;
+  if (T > 0 && (!dy || !attn || !u || !dattn || !du)) return HSTU_ERR_NULL;
+  if (misaligned(dy) || misaligned(attn) || misaligned(u) || misaligned(gamma) || misaligned(dattn) || misaligned(du) ||
+      (beta && misaligned(beta)))
+    return HSTU_ERR_SHAPE;
+  if (hstu_gated_norm_bwd_workspace_bytes(T, D) > kStaticScratchBytes) return HSTU_ERR_WORKSPACE;
+  void* partial = nullptr;
+  const int sp = static_scratch(&partial);
+  if (sp != HSTU_OK) return sp;
+  // every workgroup overwrites its whole row of partial sums and the column-sum kernel reads only the rows of this
+  // launch, so nothing left by an earlier call is ever read and nothing needs clearing
+  if (launch_gated_norm_bwd(T, D, dtype, dy, attn, u, gamma, beta, eps, dattn, du, dgamma, dbeta, (float*)partial,
                             (hipStream_t)stream) != hipSuccess)
     return HSTU_ERR_LAUNCH;
   return HSTU_OK;
