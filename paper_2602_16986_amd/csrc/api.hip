@@ -20,7 +20,7 @@ inline int64_t max_items_for(const hstu_attn_params* p, int block_rows) {
 }
 
 struct Layout {           // byte offsets inside a workspace
-  size_t header[2], items[2], seq_base[2], bias, splits, partial, splits_dq, partial_dq, dbias, total;
+  size_t header[2], items[2], seq_base[2], bias, seed, splits, partial, splits_dq, partial_dq, dbias, total;
   int max_items[2];
   int slot_cap;           // partial-sum slots of the dK/dV pass (key blocks cut along the query axis) or of the forward
   int slot_cap_dq;        // ... of the dQ pass (query blocks of a small batch cut along the key axis)
@@ -56,6 +56,8 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
   }
   l.bias = off;
   off += align_up((size_t)p->num_heads * ((size_t)p->max_seqlen + 1) * sizeof(float));
+  l.seed = off;                                        // score seeds by distance (bias + mask) of the pipelined kernels
+  off += align_up((size_t)kSeedVariants * p->num_heads * (size_t)seed_len_for(p->max_seqlen) * sizeof(float));
   if (!for_backward) {
     l.splits = off; off += align_up((size_t)(l.slot_cap / 2 + 1) * sizeof(SplitItem));
     l.partial = off;
@@ -131,6 +133,15 @@ AttnArgs make_args(const hstu_attn_params* p, const void* q, const void* k, cons
 hipError_t prepare_bias(const hstu_attn_params* p, AttnArgs& a, unsigned char* ws, const Layout& l, hipStream_t stream) {
   a.bias = nullptr;
   a.bias_stride = p->max_seqlen + 1;
+  a.seed = nullptr;
+  if (p->dtype == HSTU_BF16 && p->head_dim == 128) {   // the pipelined kernels take bias and mask from the seed tables
+    a.seed = (const float*)(ws + l.seed);
+    a.seed_len = seed_len_for(p->max_seqlen);
+    a.seed_dmax = seed_dmax_for(p->max_seqlen);
+    const hipError_t e = launch_seed_expand(p->rab_table, p->rab_bounds, p->num_buckets, p->num_heads, p->max_seqlen, a.K1,
+                                            (float*)(ws + l.seed), stream);
+    if (e != hipSuccess) return e;
+  }
   if (!p->rab_table) return hipSuccess;
   float* bias = (float*)(ws + l.bias);
   a.bias = bias;

@@ -47,7 +47,17 @@ struct AttnArgs {
   const SplitItem* splits;
   int32_t query_tail;               // forward only, > 0: compute only the last query_tail history rows and the candidates of every sequence
   float* dbias_dist;                // dQ pass, optional: sum of dS per head and distance [H, bias_stride] (zeroed by the caller)
+  // Score seeds of the pipelined kernels: bias and mask of a (position, key) pair as a function of the distance
+  // d = position - key alone, [variant][H][seed_len] floats:  seed[i] <-> d = seed_dmax - i (descending distances, so that
+  // 4 consecutive floats are the seeds of 4 consecutive keys).  d < 0 (a later key): -1e30 (which the pointwise step
+  // turns into an exact zero); 0 <= d: bias of d in units of ln 2 (0 without a bias table); variant 1 (band tiles of a
+  // semi-local mask) also has -1e30 for d >= K1.  seed_dmax >= max_seqlen + 128, seed_len >= seed_dmax + 1 + 192.
+  const float* seed;
+  int32_t seed_len, seed_dmax;
 };
+constexpr int kSeedVariants = 2;
+inline int seed_dmax_for(int max_seqlen) { return max_seqlen + 128; }
+inline int seed_len_for(int max_seqlen) { return (seed_dmax_for(max_seqlen) + 1 + 192 + 63) / 64 * 64; }
 
 // schedule.hip
 // Builds the work list for blocks of `block_rows` rows (query rows in the forward and the dQ pass,
@@ -62,6 +72,9 @@ hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], cons
                                 const int slot_cap[2], hipStream_t stream);
 hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
                               hipStream_t stream);
+// fills AttnArgs::seed (table may be nullptr: no bias)
+hipError_t launch_seed_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int max_seqlen, int K1,
+                              float* out, hipStream_t stream);
 
 // attn_core.hip
 int fwd_block_rows(int dtype, int D);     // query rows per workgroup, forward
@@ -71,6 +84,8 @@ int stream_tile_rows(int dtype, int D);   // rows of one streamed LDS tile (dQ p
 int fwd_tile_rows(int dtype, int D);      // ... in the forward
 int dkv_tile_rows(int dtype, int D);      // ... in the dK/dV pass
 hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream);
+// attn_fwd_pipe.hip: the forward for bf16 and 128 features per head (same work lists as launch_attn_fwd: 128-row blocks, 32-key tiles)
+hipError_t launch_attn_fwd_pipe(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream);
 // bias-table gradient: clear the per-distance sums, fold them into buckets (times `scale`) after the dQ pass

@@ -358,6 +358,37 @@ __global__ __launch_bounds__(256) void bias_expand_kernel(const float* __restric
   for (int h = 0; h < H; ++h) out[(size_t)h * len + x] = table[(size_t)h * nb + lo] * 1.4426950408889634f;
 }
 
+// Score seeds by distance (AttnArgs::seed): out[v][h][i], d = dmax - i.
+__global__ __launch_bounds__(256) void seed_expand_kernel(const float* __restrict__ table, const int32_t* __restrict__ bounds,
+                                                          int nb, int H, int max_seqlen, int K1, int dmax, int len,
+                                                          float* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= len) return;
+  const int d = dmax - i;
+  const int x = d < 0 ? 0 : (d > max_seqlen ? max_seqlen : d);          // distances beyond any real pair take the last real one's bias
+  int lo = 0;
+  if (table) {
+    int hi = nb;                                                         // bounds[lo] <= x < bounds[hi] (bounds[nb] = +inf)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (bounds[mid] <= x) lo = mid; else hi = mid;
+    }
+  }
+  for (int h = 0; h < H; ++h) {
+    const float b = table ? table[(size_t)h * nb + lo] * 1.4426950408889634f : 0.f;
+    out[(size_t)h * len + i] = d < 0 ? -1e30f : b;
+    out[((size_t)H + h) * len + i] = (d < 0 || (K1 >= 0 && d >= K1)) ? -1e30f : b;
+  }
+}
+
+hipError_t launch_seed_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int max_seqlen, int K1,
+                              float* out, hipStream_t stream) {
+  const int len = seed_len_for(max_seqlen);
+  hipLaunchKernelGGL(seed_expand_kernel, dim3((len + 255) / 256), dim3(256), 0, stream, table, bounds, num_buckets, H,
+                     max_seqlen, K1, seed_dmax_for(max_seqlen), len, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
                               hipStream_t stream) {
   hipLaunchKernelGGL(bias_expand_kernel, dim3((len + 255) / 256), dim3(256), 0, stream, table, bounds, num_buckets, H,
