@@ -41,9 +41,13 @@ constexpr int kTile = kBN * 256;                                       // one 32
 // bytes apart: 1 KB that the load fills plus 64 bytes that put the 16 reads of a quarter-wave on 16 different bank groups.
 constexpr int kStripCopy = 1088, kStripBytes = 4 * kStripCopy;
 constexpr int kKBase = 0, kVBase = 2 * kTile, kStripBase = 4 * kTile;
-constexpr int kSmemBytes = kStripBase + 2 * kStripBytes;
+// The last kQLds of the 8 Q fragments of a lane wait in LDS (16 bytes per lane and fragment) instead of in registers: that
+// is what lets three workgroups share a compute unit (168 registers per lane).
+constexpr int kQLds = 2;
+constexpr int kQBase = kStripBase + 2 * kStripBytes;
+constexpr int kSmemBytes = kQBase + kQLds * kThreads * 16;
 #ifndef HSTU_FP_PF
-#define HSTU_FP_PF 2
+#define HSTU_FP_PF 1
 #endif
 constexpr int kPF = HSTU_FP_PF;                                         // slots between a fragment's LDS read and its product
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
@@ -58,7 +62,7 @@ typedef __attribute__((address_space(3))) const f32x4* lds_f4;
 template <int N> using IC = std::integral_constant<int, N>;
 
 template <bool CAND>
-__global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
   const int wg = blockIdx.x;
   const int xcd = wg % kNumXcd, slot_id = wg / kNumXcd;
@@ -97,6 +101,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnAr
   }
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));      // landed before the loop: nothing in it may wait on them
+  typedef __attribute__((address_space(3))) bf16x8* lds_b8w;
+  const int qaddr = (int)(uint32_t)(uintptr_t)(lds_void)smem + kQBase + tid * 16;
+#pragma unroll
+  for (int i = 0; i < kQLds; ++i) *(lds_b8w)(uintptr_t)(uint32_t)(qaddr + i * kThreads * 16) = qf[8 - kQLds + i];
 
   f32x16 out[4];
 #pragma unroll
@@ -144,8 +152,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnAr
   uint32_t voffK1 = voffK + 16u * rowbK, voffV1 = voffV + 16u * rowbV;
   uint32_t voffS = 16u * (uint32_t)lane + 4u * (uint32_t)wave;           // this wave loads copy `wave` of the strip
   asm volatile("" : "+v"(voffK), "+v"(voffV), "+v"(voffK1), "+v"(voffV1), "+v"(voffS));
+  // (every word goes through readfirstlane: the descriptor of a load must sit in scalar registers, and the compiler is
+  // otherwise free to assemble a uniform 128-bit value in vector registers; on a scalar input it is a plain copy)
   auto make_rsrc = [&](uint64_t addr, uint32_t bytes) -> i32x4 {
-    return (i32x4){(int)(uint32_t)addr, (int)(uint32_t)(addr >> 32), (int)bytes, 0x00020000};
+    return (i32x4){__builtin_amdgcn_readfirstlane((int)(uint32_t)addr), __builtin_amdgcn_readfirstlane((int)(uint32_t)(addr >> 32)),
+                   __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
   };
   // (M0 = a per-wave base + a constant: one scalar instruction; one idle cycle between the write of M0 and its use)
   const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void)smem;
@@ -160,26 +171,42 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnAr
   // table that applies (band tiles of a semi-local mask: the one that also masks by distance) and the strip origin.
   // A sub-block beyond the list gets empty ranges: its loads are still issued (the waits count loads), read zeros and
   // land in stages whose products then contribute nothing (score 0, SiLU(0) = 0).
-  struct Src { i32x4 k, v, seed; uint32_t s_off; int yt; };
+  struct Rows { uint64_t addr; int left; };                             // a wave's rows of one tile: first row, rows left in the sequence (<= 0: none)
+  struct Src { Rows k, v; uint64_t seed; uint32_t seed_bytes, s_off; int yt; };
   auto src_of = [&](int idx) -> Src {
     const bool valid = idx < n;
     const int yt = valid ? tile_of(idx) : 0;
     const int yrow = yt * kBN + 4 * wave;
-    const uint32_t left = valid ? (uint32_t)max(L - yrow, 0) : 0u;
+    const int left = valid ? L - yrow : 0;
     const bool band = g.K1 >= 0 && yt >= tr.b0 && yt < tr.b1;
     Src r;
-    r.k = make_rsrc((uint64_t)(uintptr_t)Kp + (uint64_t)(uint32_t)yrow * rowbK, left * rowbK);
-    r.v = make_rsrc((uint64_t)(uintptr_t)Vp + (uint64_t)(uint32_t)yrow * rowbV, left * rowbV);
-    r.seed = make_rsrc((uint64_t)(uintptr_t)(seed_h + (band ? seed_var1 : 0)), valid ? seed_bytes : 0u);
+    r.k = {(uint64_t)(uintptr_t)Kp + (uint64_t)(uint32_t)yrow * rowbK, left};
+    r.v = {(uint64_t)(uintptr_t)Vp + (uint64_t)(uint32_t)yrow * rowbV, left};
+    r.seed = (uint64_t)(uintptr_t)(seed_h + (band ? seed_var1 : 0));
+    r.seed_bytes = valid ? seed_bytes : 0u;
     // strip index s <-> distance d0 - s, d0 = x0v + kBX - 1 - yt * kBN  <->  table index seed_dmax - d0 + s
     r.s_off = 4u * (uint32_t)(a.seed_dmax - (x0v + (kBX - 1) - yt * kBN));
     r.yt = valid ? yt : kNoTile;
     return r;
   };
+  // The sub-block after `prev` (list index idx): nearly always the next tile of the same sequence, whose descriptors are
+  // a few scalar additions away (one 32-row tile further down, 32 distances closer); anything else is built from scratch.
+  const uint32_t stepK = 32u * rowbK, stepV = 32u * rowbV;
+  auto next_src = [&](const Src& prev, int idx) -> Src {
+    const int yt = idx < n ? tile_of(idx) : kNoTile;
+    if (__builtin_expect(yt != prev.yt + 1 || (g.K1 >= 0 && yt == tr.b0), 0)) return src_of(idx);
+    Src r = prev;
+    r.k.addr = prev.k.addr + stepK; r.k.left = prev.k.left - kBN;
+    r.v.addr = prev.v.addr + stepV; r.v.left = prev.v.left - kBN;
+    r.s_off = prev.s_off + 4u * kBN;
+    r.yt = yt;
+    return r;
+  };
   // piece c (0, 1): the 4-row group 4 c + wave of the tile
-  auto load_k = [&](const Src& sr, int stage, int c) { dma16(sr.k, c ? voffK1 : voffK, m0_rows, (uint32_t)(kKBase + stage * kTile + 4096 * c)); };
-  auto load_v = [&](const Src& sr, int stage, int c) { dma16(sr.v, c ? voffV1 : voffV, m0_rows, (uint32_t)(kVBase + stage * kTile + 4096 * c)); };
-  auto load_strip = [&](const Src& sr, int stage) { dma16(sr.seed, voffS + sr.s_off, m0_strip, (uint32_t)(stage * kStripBytes)); };
+  auto load_k = [&](const Src& sr, int stage, int c) { dma16(make_rsrc(sr.k.addr, (uint32_t)max(sr.k.left, 0) * rowbK), c ? voffK1 : voffK, m0_rows, (uint32_t)(kKBase + stage * kTile + 4096 * c)); };
+  auto load_vd = [&](const Rows& vd, int stage, int c) { dma16(make_rsrc(vd.addr, (uint32_t)max(vd.left, 0) * rowbV), c ? voffV1 : voffV, m0_rows, (uint32_t)(kVBase + stage * kTile + 4096 * c)); };
+  auto load_v = [&](const Src& sr, int stage, int c) { load_vd(sr.v, stage, c); };
+  auto load_strip = [&](const Src& sr, int stage) { dma16(make_rsrc(sr.seed, sr.seed_bytes), voffS + sr.s_off, m0_strip, (uint32_t)(stage * kStripBytes)); };
 
   // ---- LDS fragment addresses of stage 0 (the stage and the position inside the tile are immediate offsets).
   // Row r stores its logical 16-byte chunk c at chunk c ^ (4 (r % 4) + (r / 4) % 4).
@@ -236,10 +263,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnAr
   };
 
   // ---- prologue: K and strip of sub-blocks 0 and 1.  src0 / src1 describe the sub-blocks s and s + 1 of the coming step.
-  Src src0 = src_of(0), src1 = src_of(1);
-  load_k(src0, 0, 0); load_k(src0, 0, 1);
-  load_k(src1, 1, 0); load_k(src1, 1, 1);
-  load_strip(src0, 0); load_strip(src1, 1);
+  // Carried from step to step: `cur` describes the newest sub-block whose K and strip loads were issued (s + 1 when step
+  // s starts); of the two before it only the V descriptors (their V loads are issued two steps after their K loads).
+  Src cur = src_of(0);
+  Rows vdesc0 = cur.v, vdesc1;                                         // V of sub-blocks s and s + 1
+  const int yt_first = cur.yt;
+  load_k(cur, 0, 0); load_k(cur, 0, 1); load_strip(cur, 0);
+  cur = next_src(cur, 1);
+  vdesc1 = cur.v;
+  load_k(cur, 1, 0); load_k(cur, 1, 1); load_strip(cur, 1);
   {                                                                     // V stage 1 is read by step 0 ("sub-block -1"): zeros
     const Src none = src_of(n);
     load_v(none, 1, 0); load_v(none, 1, 1);
@@ -249,7 +281,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnAr
 #pragma unroll
   for (int i = 0; i < kPF; ++i) kfn[i] = kfrag(0, i);
   seed(sacc[0], 0);
-  if (nfast == 0 && n > 0) mask_seed(sacc[0], src0.yt);
+  if (nfast == 0 && n > 0) mask_seed(sacc[0], yt_first);
 #pragma unroll
   for (int r = 0; r < 16; ++r) sacc[1][r] = kMasked;                    // "sub-block -1": contributes nothing
 #pragma unroll
@@ -275,15 +307,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnAr
     constexpr bool PATCH = decltype(patch_c)::value;
     // ---------------- first half: S(s) products, SiLU of keys 16..31 of s - 1
     bf16x8 kf[kPF + 1], vf[kPF + 1];                                    // fragments are fetched kPF slots ahead of their product
+    bf16x8 qx[kQLds];
 #pragma unroll
     for (int i = 0; i < kPF; ++i) kf[i] = kfn[i];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if (i < 2) load_v(src0, P, i);
+      if (i < 2) load_vd(vdesc0, P, i);
+      if (i >= 8 - kQLds - 2 && i < 8 - 2) qx[i - (8 - kQLds - 2)] = *(lds_b8)(uintptr_t)(uint32_t)(qaddr + (i - (8 - kQLds - 2)) * kThreads * 16);
       if (i + kPF < 8) kf[(i + kPF) % (kPF + 1)] = kfrag(P, i + kPF);
       else vf[(i + kPF - 8) % (kPF + 1)] = vfrag(P ^ 1, (i + kPF - 8) >> 2, (i + kPF - 8) & 3);
       __builtin_amdgcn_sched_barrier(0);
-      sacc[P] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (kPF + 1)], qf[i], sacc[P], 0, 0, 0);
+      sacc[P] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (kPF + 1)], i < 8 - kQLds ? qf[i] : qx[i - (8 - kQLds)], sacc[P], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       {
         const float pp = silu_roll(sacc[P ^ 1][8 + i]);                 // finishes the previous score (keys 16.. of s - 1, or key 15 of its first half)
@@ -297,15 +331,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnAr
     __syncthreads();
 
     // ---------------- second half: O += V(s-1)^T P(s-1), SiLU of keys 0..15 of s
-    const Src src2 = src_of(s + 2);
+    const int yt_seed = cur.yt;                                         // sub-block s + 1, seeded in this half
+    cur = next_src(cur, s + 2);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       if (j == 4) {                                                     // (the last 8 scores of s - 1 went into P in the first half)
         seed(sacc[P ^ 1], P ^ 1);
-        if (PATCH) { if (s + 1 >= nfast && s + 1 < n) mask_seed(sacc[P ^ 1], src1.yt); }
+        if (PATCH) { if (s + 1 >= nfast && s + 1 < n) mask_seed(sacc[P ^ 1], yt_seed); }
       }
-      if (j < 2) load_k(src2, P, j);
-      else if (j == 2) load_strip(src2, P);
+      if (j < 2) load_k(cur, P, j);
+      else if (j == 2) load_strip(cur, P);
       if (j + kPF < 8) vf[(j + kPF) % (kPF + 1)] = vfrag(P ^ 1, (j + kPF) >> 2, (j + kPF) & 3);
       else kfn[j + kPF - 8] = kfrag(P ^ 1, j + kPF - 8);
       __builtin_amdgcn_sched_barrier(0);
@@ -325,7 +360,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_pipe_kernel(const AttnAr
     }
     asm volatile("s_waitcnt vmcnt(3)" ::: "memory");                    // V(s) landed (only the 3 loads of this half may still fly)
     __syncthreads();
-    src0 = src1; src1 = src2;
+    vdesc0 = vdesc1; vdesc1 = cur.v;
   };
 
   // steps whose seeded sub-block needs no patch, in pairs; then the rest (patched sub-blocks and the two draining steps)
