@@ -21,15 +21,31 @@ import numpy as np
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
-# bytes behind the L2 per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/attention_c3_dense_counters.md (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration
-# against a plain 1 GiB copy); only known for the workload that was profiled
-MEASURED_TRAFFIC_BYTES = {("C3-dense", "attn_fwd"): 3.283e9 + 0.090e9, ("C3-dense", "attn_bwd_dq"): 4.008e9 + 0.090e9,
-                          ("C3-dense", "attn_bwd_dkdv"): 3.266e9 + 0.182e9,
-                          # profiles/truncation_at_3072_512.md
-                          ("AT-3072-512", "truncate_fwd"): 0.1343e9 + 0.1342e9, ("AT-3072-512", "truncate_bwd"): 0.1343e9 + 0.5240e9,
-                          # profiles/fp8_gemm_1m_512.md
-                          ("1M-512", "fp8_gemm_bias2d"): 1.658e9 + 1.074e9}
+# Bytes behind the L2 per launch (read + written) come from rocprofv3 FETCH_SIZE / WRITE_SIZE runs whose summaries sit under
+# profiles/; profiles/traffic.json holds the figures together with a hash of the kernel sources they were measured with.
+# When the sources have changed since, the figure is stale and `traffic` is reported as null.
+ROOT = os.path.dirname(os.path.abspath(__file__))
+
+
+def kernel_sources_hash():
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2602_16986_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload, kernel):
+    try:
+        t = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+    except (OSError, ValueError):
+        return None
+    if t.get("kernel_sources_sha256") != kernel_sources_hash():
+        return None
+    return t.get("bytes_per_launch", {}).get(workload, {}).get(kernel)
 
 
 def parse():
@@ -58,6 +74,8 @@ def parse():
     ap.add_argument("--reuse-schedule", action="store_true",
                     help="attention op: after the warm-up the steps reuse the work lists in the workspaces (the layers of one model "
                          "after the first); reported next to the headline, never as it: `value` of the default run includes the scheduler")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="default run (C3-dense): skip the short timed steps of the other configurations (C3-sparse, C4, C5, C2)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (profiling aid: calibrates the HBM byte counters)")
     return ap.parse_args()
@@ -159,7 +177,7 @@ def bench_truncate(args):
            "config": {"workload": c.name, "B": len(c.lengths), "T": int(x.shape[0]), "kept_rows": kept, "keep": c.keep,
                       "row_bytes": row},
            "roofline": {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": achieved / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((c.name, dom))},
+                        "frac": achieved / PEAK_HBM_GBS, "traffic": measured_traffic(c.name, dom)},
            "kernel_ms": kern,
            "kernel_gbs": {k: algo[k] / (kern[k] * 1e-3) / 1e9 for k in algo}}
     if not args.no_cpu_baseline:
@@ -221,7 +239,7 @@ def bench_fp8_gemm(args):
            "data": "synthetic", "config": {"workload": f"fp8-gemm-{args.fp8_shape}", "m": M, "k": KN, "n": KN},
            "paper_h100_tflops": PAPER_FP8_GEMM_TFLOPS[args.fp8_shape],
            "roofline": {"kernel": "fp8_gemm_bias2d", "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": achieved / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((args.fp8_shape, "fp8_gemm_bias2d"))},
+                        "frac": achieved / PEAK_HBM_GBS, "traffic": measured_traffic(args.fp8_shape, "fp8_gemm_bias2d")},
            "kernel_ms": {"fp8_gemm_bias2d": kms, "rowwise_quant_of_A": ms_quant},
            "mfma_frac_of_fp8_peak": flops / (kms * 1e-3) / 1e12 / 5000.0,
            "quant_gbs": float(M) * KN * 3 / (ms_quant * 1e-3) / 1e9}
@@ -292,6 +310,37 @@ def bench_layer(args):
     print(json.dumps(out))
 
 
+def other_configs(args, torch, hb, flops, workloads, DeviceWorkload, peak):
+    """Short timed steps of the configurations the headline is not quoted on: the same step loop, fewer steps."""
+    res = {}
+    for name in ("C3-sparse", "C4", "C5", "C2"):
+        w = workloads.config(name)
+        fl = flops.attention_flops(w)
+        dw = DeviceWorkload(w)
+        step = dw.layer_step if w.backward else dw.attn_fwd
+        for _ in range(3):
+            step()
+        ms = time_loop(step, 10, torch)
+        hb.hstu_profile_enable(True)
+        kern = {}
+        for _ in range(5):
+            step()
+            for kname, t in hb.hstu_profile_read():
+                kern.setdefault(kname, []).append(t)
+        hb.hstu_profile_enable(False)
+        kern = {k: float(np.mean(v)) for k, v in kern.items()}
+        useful = fl["fwd"] + (fl["bwd"] if w.backward else 0.0)
+        r = {"pass": "fwd+bwd+epilogue" if w.backward else "fwd", "ms_per_step": ms, "tflops": useful / (ms * 1e-3) / 1e12,
+             "frac_of_peak": useful / (ms * 1e-3) / 1e12 / peak, "unmasked_pairs": fl["pairs"],
+             "fwd_tflops": fl["fwd"] / (kern["attn_fwd"] * 1e-3) / 1e12, "kernel_ms": kern}
+        if w.backward:
+            r["bwd_tflops"] = fl["bwd"] / ((kern["attn_bwd_dq"] + kern["attn_bwd_dkdv"]) * 1e-3) / 1e12
+        res[name] = r
+        del dw
+        torch.cuda.empty_cache()
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -357,13 +406,17 @@ def main():
     value = useful / (ms_step * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
 
-    # roofline of the dominant kernel.  Algorithmic FLOPs per launch = products the kernel owes per
-    # unmasked pair: forward 2 (4d), dQ pass 3 (6d: S, dP, dQ), dK/dV pass 4 (8d: S, dP, dK, dV).
-    algo = {"attn_fwd": 4.0, "attn_bwd_dq": 6.0, "attn_bwd_dkdv": 8.0}
-    dom = max((k for k in kern if k in algo), key=lambda k: kern[k])
-    achieved = algo[dom] * w.d * fl["pairs"] / (kern[dom] * 1e-3) / 1e12
+    # Roofline of the dominant kernel, in USEFUL FLOPs: of the 10 d the backward owes per unmasked pair (S, dP, dV, dK,
+    # dQ) the dK/dV pass is credited with dV, dK and half of the S and dP that both passes compute (6 d), the dQ pass with dQ
+    # and the other half (4 d); the forward with its 4 d.  What the passes execute (4 d, 6 d, 8 d) is reported beside it.
+    useful_d = {"attn_fwd": 4.0, "attn_bwd_dq": 4.0, "attn_bwd_dkdv": 6.0}
+    executed_d = {"attn_fwd": 4.0, "attn_bwd_dq": 6.0, "attn_bwd_dkdv": 8.0}
+    dom = max((k for k in kern if k in useful_d), key=lambda k: kern[k])
+    achieved = useful_d[dom] * w.d * fl["pairs"] / (kern[dom] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))}
+                "frac": achieved / peak, "traffic": measured_traffic(w.name, dom),
+                "flops_basis": "useful: %g d per unmasked pair and head" % useful_d[dom]}
+    executed = {k: executed_d[k] * w.d * fl["pairs"] / (kern[k] * 1e-3) / 1e12 / peak for k in kern if k in executed_d}
 
     sched = hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)
     eb = flops.epilogue_bytes(w)
@@ -379,7 +432,7 @@ def main():
         "frac_of_peak": value / peak,
         "fwd_tflops": fl["fwd"] / (kern["attn_fwd"] * 1e-3) / 1e12,
         "fwd_frac_of_peak": fl["fwd"] / (kern["attn_fwd"] * 1e-3) / 1e12 / peak,
-        "roofline": roofline,
+        "roofline": roofline, "mfma_executed_frac": executed,
         "entry_ms": parts, "kernel_ms": kern,
         "schedule": {**sched, "skipped_tile_frac": 1.0 - sched["tiles"] / max(sched["dense_tiles"], 1)},
     }
@@ -390,6 +443,11 @@ def main():
         out["bwd_frac_of_peak"] = out["bwd_tflops"] / peak
         out["epilogue_gbs"] = {"fwd": eb["fwd"] / (kern["gated_norm_fwd"] * 1e-3) / 1e9,
                                "bwd": eb["bwd"] / (kern["gated_norm_bwd"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS}
+    # the bias / seed expansion kernels (latency-bound: tens of KB to a few MB per launch)
+    from paper_2602_16986_amd.flops import expand_bytes
+    out["bias_expand_gbs"] = {k: expand_bytes(w, k) / (kern[k] * 1e-3) / 1e9 for k in ("bias_expand_fwd", "bias_expand_bwd") if k in kern}
+    if w.name == "C3-dense" and do_bwd and not args.no_other_configs and args.query_tail == 0 and not args.bias_grad:
+        out["other_configs"] = other_configs(args, torch, hb, flops, workloads, DeviceWorkload, peak)
     if ms_reuse is not None:
         useful = fl["fwd"] + (fl["bwd"] if do_bwd else 0.0)
         out["with_reused_schedule"] = {"ms_per_step": ms_reuse, "tflops": useful / (ms_reuse * 1e-3) / 1e12}

@@ -130,17 +130,17 @@ AttnArgs make_args(const hstu_attn_params* p, const void* q, const void* k, cons
 }
 
 // Enqueues the bias expansion (if any) and fills the bias fields.
-hipError_t prepare_bias(const hstu_attn_params* p, AttnArgs& a, unsigned char* ws, const Layout& l, hipStream_t stream) {
+hipError_t prepare_bias(const hstu_attn_params* p, AttnArgs& a, unsigned char* ws, const Layout& l, hipStream_t stream,
+                        bool for_forward) {
   a.bias = nullptr;
   a.bias_stride = p->max_seqlen + 1;
   a.seed = nullptr;
-  if (p->dtype == HSTU_BF16 && p->head_dim == 128) {   // the pipelined kernels take bias and mask from the seed tables
+  if (p->dtype == HSTU_BF16 && p->head_dim == 128 && p->query_tail == 0 && for_forward) {   // the pipelined forward takes bias and mask from the seed tables
     a.seed = (const float*)(ws + l.seed);
     a.seed_len = seed_len_for(p->max_seqlen);
     a.seed_dmax = seed_dmax_for(p->max_seqlen);
-    const hipError_t e = launch_seed_expand(p->rab_table, p->rab_bounds, p->num_buckets, p->num_heads, p->max_seqlen, a.K1,
-                                            (float*)(ws + l.seed), stream);
-    if (e != hipSuccess) return e;
+    return launch_seed_expand(p->rab_table, p->rab_bounds, p->num_buckets, p->num_heads, p->max_seqlen, a.K1,
+                              (float*)(ws + l.seed), stream);           // (that kernel needs no other table)
   }
   if (!p->rab_table) return hipSuccess;
   float* bias = (float*)(ws + l.bias);
@@ -246,8 +246,8 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
       return HSTU_ERR_LAUNCH;
   }
   {
-    ProfScope ps("bias_expand", stream);
-    if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    ProfScope ps("bias_expand_fwd", stream);
+    if (prepare_bias(p, a, ws, l, stream, true) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   {
     ProfScope ps("attn_fwd", stream);                      // includes the kernel that combines the pieces of cut blocks
@@ -281,8 +281,8 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
   a.dout = dout; a.dq = dq; a.dk = dk; a.dv = dv;
   const int tile = stream_tile_rows(p->dtype, p->head_dim);
   {
-    ProfScope ps("bias_expand", stream);
-    if (prepare_bias(p, a, ws, l, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    ProfScope ps("bias_expand_bwd", stream);
+    if (prepare_bias(p, a, ws, l, stream, false) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   if (!p->reuse_schedule) {
     ProfScope ps("schedule_bwd", stream);

@@ -21,7 +21,6 @@
 // wants for its B operand, so P / dS never travel through LDS; the streamed tile is read
 // once more through the LDS transpose loads (ds_read_b64_tr_b16) to form the A operand of
 // the second product.  The fp32 instantiation uses v_mfma_f32_32x32x2_f32 the same way.
-#include <cstdlib>
 #include <type_traits>
 
 #include "hstu_common.h"
@@ -1005,7 +1004,9 @@ int fwd_tile_rows(int dtype, int D) { return dtype == 0 ? (D == 128 ? 32 : 64) :
 int dkv_tile_rows(int dtype, int D) { return dtype == 0 ? (D == 128 ? 32 : 64) : 32; }
 
 hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream) {
-  if (dtype == 0 && a.D == 128 && !getenv("HSTU_FWD_OLD")) return launch_attn_fwd_pipe(a, stream);
+  // bf16 with 128 features: the pipelined kernel (a forward restricted to a query tail keeps the kernel below, which
+  // skips the waves in front of the tail)
+  if (dtype == 0 && a.D == 128 && a.seed && a.query_tail == 0) return launch_attn_fwd_pipe(a, stream);
   if (a.num_targets) return dispatch<kFwd, kFwdWavesBf16, kFwdWavesFp32, false, true>(a, dtype, stream);
   return dispatch<kFwd, kFwdWavesBf16, kFwdWavesFp32>(a, dtype, stream);
 }

@@ -53,3 +53,13 @@ def bytes_per_elem(dtype: str) -> int:
 def epilogue_bytes(w):
     e = bytes_per_elem(w.dtype) * w.T * w.H * w.d
     return {"fwd": 3 * e + 8 * w.T, "bwd": 5 * e}
+
+
+def expand_bytes(w, kernel: str) -> float:
+    """Bytes the expansion kernel in front of an attention pass writes: the distance-indexed seed tables of the pipelined
+    forward (bf16, 128 features per head: two variants of max_seqlen + 128 + 1 + 192 entries per head, rounded up to 64), or
+    the plain per-distance bias table (max_seqlen + 1 entries per head)."""
+    if kernel == "bias_expand_fwd" and w.dtype == "bf16" and w.d == 128:
+        seed_len = (w.max_seqlen + 128 + 1 + 192 + 63) // 64 * 64
+        return 2.0 * w.H * seed_len * 4
+    return float(w.H) * (w.max_seqlen + 1) * 4
