@@ -211,10 +211,12 @@ int hstu_truncate_bwd(int32_t batch, int64_t total_tokens, const int32_t* seq_of
  * straight into the column blocks of one gradient buffer (no concatenation).
  *
  * The four projections run through hipBLASLt (plain library GEMMs); the first call on a device creates a
- * hipBLASLt handle, and the first call with a new shape makes the matmul plans: it runs the library's candidate
- * kernels on `stream`, waits for them and keeps the fastest (so that call allocates inside the GEMM library,
- * blocks the host and must not be captured into a graph); later calls with the same shapes allocate nothing and
- * only enqueue.  Not thread-safe.  HSTU_ERR_UNSUPPORTED if the library has no kernel for a shape.
+ * hipBLASLt handle.  The GEMM kernels are chosen once per SHAPE CLASS, which is the layer's dimensions together with
+ * the token count T rounded up to a power of two: the first call of a class runs the library's candidate kernels on
+ * `stream`, waits for them and keeps the fastest (that call allocates inside the GEMM library, blocks the host and
+ * must not be captured into a graph; hstu_layer_gemm_tunings counts these events).  Every later call of the class,
+ * whatever its exact T, only builds its descriptors on the host and enqueues.  Not thread-safe.
+ * HSTU_ERR_UNSUPPORTED if the library has no kernel for a shape.
  * T = 0: the forward writes nothing, the backward zeroes the weight gradients.
  */
 typedef struct hstu_layer_params {
@@ -249,6 +251,10 @@ int hstu_layer_fwd(const hstu_layer_params* p, const void* z, void* out, void* u
 int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_saved, const void* attn_saved,
                    const float* mean, const float* rstd, const void* dout, void* dz, float* d_norm_w, float* d_w1,
                    float* d_gated_norm_w, float* d_w2, void* workspace, size_t workspace_bytes, void* stream);
+
+/* How many times this process has timed GEMM candidates so far (once per GEMM of a new shape class, see above): a
+ * caller that must not block, or that is about to capture a graph, can check that a warm-up call left nothing to tune. */
+int64_t hstu_layer_gemm_tunings(void);
 
 /*
  * FP8 around the layer's two projections (paper Section 4.2.2, "Mixed-Precision Training and Inference", and the FP8

@@ -90,6 +90,8 @@ def _load() -> ctypes.CDLL:
     lib.hstu_layer_fwd.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hstu_layer_bwd.restype = ctypes.c_int
     lib.hstu_layer_bwd.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.hstu_layer_gemm_tunings.restype = ctypes.c_int64
+    lib.hstu_layer_gemm_tunings.argtypes = []
     lib.hstu_norm_quant_fp8.restype = ctypes.c_int
     lib.hstu_norm_quant_fp8.argtypes = [i64, i32, i32, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
     lib.hstu_fp8_gemm_bias2d.restype = ctypes.c_int
@@ -107,7 +109,7 @@ EXPORTS = ["hstu_attn_workspace_bytes", "hstu_attn_fwd", "hstu_attn_bwd", "hstu_
            "hstu_gated_norm_bwd_static_max_bytes", "hstu_gated_norm_bwd_static",
            "hstu_attn_schedule_stats", "hstu_profile_enable", "hstu_profile_read",
            "hstu_truncate_offsets", "hstu_truncate_fwd", "hstu_truncate_bwd",
-           "hstu_layer_workspace_bytes", "hstu_layer_fwd", "hstu_layer_bwd",
+           "hstu_layer_workspace_bytes", "hstu_layer_fwd", "hstu_layer_bwd", "hstu_layer_gemm_tunings",
            "hstu_norm_quant_fp8", "hstu_fp8_gemm_bias2d"]
 
 
@@ -326,6 +328,11 @@ def hstu_layer_bwd(prob: LayerProblem, z, u_saved, attn_saved, mean, rstd, dout,
                              workspace.numel(), _stream(stream))
     if st != HSTU_OK:
         raise HstuError(st, "hstu_layer_bwd")
+
+
+def hstu_layer_gemm_tunings() -> int:
+    """How many times the layer's GEMMs have timed candidate kernels (and blocked the host) in this process."""
+    return int(_lib.hstu_layer_gemm_tunings())
 
 
 def hstu_norm_quant_fp8(a, u, gamma, beta, eps, q, q_scale, mean=None, rstd=None, stream=None) -> None:

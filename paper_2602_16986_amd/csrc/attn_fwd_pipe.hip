@@ -53,6 +53,22 @@ constexpr int kPF = HSTU_FP_PF;                                         // slots
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 constexpr float kMasked = -1e30f;
 constexpr int kNoTile = 1 << 28;
+// Measurement builds only (results are wrong): HSTU_FWD_ABLATE is a bit mask of parts of the tile loop to leave out, to
+// see what each costs in time and in the clock the chip sustains.  1: the global -> LDS loads of the loop; 2: the two
+// transcendentals of SiLU; 4: the LDS reads of K / V fragments and seeds (16 / 32 / 64: those of K / of V / of the seeds
+// alone); 8: the matrix instructions; 128: the K fragments are read but a constant register goes into the product in
+// their place (the reads stay, the operand stops changing).  Every memory access an ablated build still makes is one
+// the normal build makes.
+#ifndef HSTU_FWD_ABLATE
+#define HSTU_FWD_ABLATE 0
+#endif
+constexpr bool kNoDma = HSTU_FWD_ABLATE & 1, kNoSilu = HSTU_FWD_ABLATE & 2, kNoMfma = HSTU_FWD_ABLATE & 8;
+constexpr bool kNoLdsK = HSTU_FWD_ABLATE & (4 | 16), kNoLdsV = HSTU_FWD_ABLATE & (4 | 32), kNoLdsSeed = HSTU_FWD_ABLATE & (4 | 64);
+template <class T> __device__ __forceinline__ T undefined_value() { T v; asm volatile("" : "=v"(v)); return v; }
+__device__ __forceinline__ f32x16 mfma(bf16x8 x, bf16x8 y, f32x16 acc) {
+  if constexpr (kNoMfma) { asm volatile("" :: "v"(x), "v"(y)); return acc; }
+  else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc, 0, 0, 0);
+}
 
 typedef __attribute__((address_space(3))) void* lds_void;
 typedef __attribute__((address_space(3))) short4v* lds_s4;
@@ -222,9 +238,18 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
     asm volatile("" : "+v"(kaddr[i]), "+v"(vaddr[i]));
   }
   const int saddr = (int)smem_base + kStripBase + (strip_s0 & 3) * kStripCopy + (strip_s0 & ~3) * 4;
-  auto kfrag = [&](int stage, int ks) -> bf16x8 { return *(lds_b8)(uintptr_t)(uint32_t)(kaddr[ks] + stage * kTile); };
+  auto kfrag = [&](int stage, int ks) -> bf16x8 {
+    if constexpr (kNoLdsK) return undefined_value<bf16x8>();
+    if constexpr ((HSTU_FWD_ABLATE & 128) != 0) {
+      const bf16x8 f = *(lds_b8)(uintptr_t)(uint32_t)(kaddr[ks] + stage * kTile);
+      asm volatile("" :: "v"(f));
+      return undefined_value<bf16x8>();
+    }
+    return *(lds_b8)(uintptr_t)(uint32_t)(kaddr[ks] + stage * kTile);
+  };
   // A operand of an output product: features 32 ob .. 32 ob + 31 (rows) x keys 16 ks2 + 4 hf + {0..3}, + 8 + {0..3}
   auto vfrag = [&](int stage, int ks2, int ob) -> bf16x8 {
+    if constexpr (kNoLdsV) return undefined_value<bf16x8>();
     const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(uint32_t)(vaddr[2 * ob] + stage * kTile + ks2 * 4096));
     const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(uint32_t)(vaddr[2 * ob + 1] + stage * kTile + ks2 * 4096 + 2048));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -257,7 +282,7 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
   auto seed = [&](f32x16& acc, int stage) {
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
-      const f32x4 bv = *(lds_f4)(uintptr_t)(uint32_t)(saddr + stage * kStripBytes + 32 * q4);
+      const f32x4 bv = kNoLdsSeed ? undefined_value<f32x4>() : *(lds_f4)(uintptr_t)(uint32_t)(saddr + stage * kStripBytes + 32 * q4);
       acc[4 * q4 + 0] = bv[0]; acc[4 * q4 + 1] = bv[1]; acc[4 * q4 + 2] = bv[2]; acc[4 * q4 + 3] = bv[3];
     }
   };
@@ -292,9 +317,9 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
   // the transcendental right in front of it.  Returns the finished previous score.
   float st_t = kMasked, st_r = 0.f, st_p = 0.f;
   auto silu_roll = [&](float t) -> float {
-    const float e = __builtin_amdgcn_exp2f(-t);
+    const float e = kNoSilu ? -t : __builtin_amdgcn_exp2f(-t);
     const float pp = st_t * st_r;
-    const float r = __builtin_amdgcn_rcpf(1.0f + e);
+    const float r = kNoSilu ? 1.0f + e : __builtin_amdgcn_rcpf(1.0f + e);
     st_t = t; st_r = r;
     asm volatile("" : "+v"(st_r));                                       // the pointwise work stays in its slot
     return pp;
@@ -312,12 +337,12 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
     for (int i = 0; i < kPF; ++i) kf[i] = kfn[i];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if (i < 2) load_vd(vdesc0, P, i);
+      if (i < 2 && !kNoDma) load_vd(vdesc0, P, i);
       if (i >= 8 - kQLds - 2 && i < 8 - 2) qx[i - (8 - kQLds - 2)] = *(lds_b8)(uintptr_t)(uint32_t)(qaddr + (i - (8 - kQLds - 2)) * kThreads * 16);
       if (i + kPF < 8) kf[(i + kPF) % (kPF + 1)] = kfrag(P, i + kPF);
       else vf[(i + kPF - 8) % (kPF + 1)] = vfrag(P ^ 1, (i + kPF - 8) >> 2, (i + kPF - 8) & 3);
       __builtin_amdgcn_sched_barrier(0);
-      sacc[P] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (kPF + 1)], i < 8 - kQLds ? qf[i] : qx[i - (8 - kQLds)], sacc[P], 0, 0, 0);
+      sacc[P] = mfma(kf[i % (kPF + 1)], i < 8 - kQLds ? qf[i] : qx[i - (8 - kQLds)], sacc[P]);
       __builtin_amdgcn_sched_barrier(0);
       {
         const float pp = silu_roll(sacc[P ^ 1][8 + i]);                 // finishes the previous score (keys 16.. of s - 1, or key 15 of its first half)
@@ -339,15 +364,15 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
         seed(sacc[P ^ 1], P ^ 1);
         if (PATCH) { if (s + 1 >= nfast && s + 1 < n) mask_seed(sacc[P ^ 1], yt_seed); }
       }
-      if (j < 2) load_k(cur, P, j);
-      else if (j == 2) load_strip(cur, P);
+      if (j < 2 && !kNoDma) load_k(cur, P, j);
+      else if (j == 2 && !kNoDma) load_strip(cur, P);
       if (j + kPF < 8) vf[(j + kPF) % (kPF + 1)] = vfrag(P ^ 1, (j + kPF) >> 2, (j + kPF) & 3);
       else kfn[j + kPF - 8] = kfrag(P ^ 1, j + kPF - 8);
       __builtin_amdgcn_sched_barrier(0);
       {
         const uint32_t* pk = (j < 4) ? plo[P ^ 1] : phi;
         const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
-        out[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j % (kPF + 1)], pb, out[j & 3], 0, 0, 0);
+        out[j & 3] = mfma(vf[j % (kPF + 1)], pb, out[j & 3]);
       }
       __builtin_amdgcn_sched_barrier(0);
       {

@@ -300,4 +300,6 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
   return HSTU_OK;
 }
 
+int64_t hstu_layer_gemm_tunings(void) { return (int64_t)gemm_bf16_tunings(); }
+
 }  // extern "C"

@@ -100,6 +100,19 @@ def test_layer_backward_twice_is_identical(hb):
         assert torch.equal(a, b)
 
 
+def test_layer_new_token_count_of_a_known_class_tunes_nothing(hb):
+    """The GEMM kernels are chosen once per shape class (layer dimensions, token count rounded up to a power of two).
+    A batch with another token count of the same class must not time candidates again (that would block the host on
+    every jagged batch), and its results must still match the oracle."""
+    run_case(wl.build_layer("class-a", [300, 0, 150, 210], 2, 64, 320, seed=11, K1=64, K2=16))     # T = 660: class 1024
+    tuned = hb.hstu_layer_gemm_tunings()
+    assert tuned > 0
+    run_case(wl.build_layer("class-b", [401, 77, 333], 2, 64, 320, seed=12, K1=64, K2=16))         # T = 811: same class
+    assert hb.hstu_layer_gemm_tunings() == tuned
+    run_case(wl.build_layer("class-c", [700, 500], 2, 64, 320, seed=13, K1=64, K2=16))             # T = 1200: class 2048
+    assert hb.hstu_layer_gemm_tunings() > tuned
+
+
 def test_layer_empty_batch(hb):
     from paper_2602_16986_amd.runner import DeviceLayer
     dl = DeviceLayer(wl.build_layer("empty", [0, 0], 2, 64, 96))
