@@ -26,6 +26,10 @@
 #include "hstu_common.h"
 #include "hstu_kernels.h"
 
+#ifndef HSTU_DKDV_PF
+#define HSTU_DKDV_PF 2
+#endif
+
 namespace hstu {
 
 enum { kFwd = 0, kBwdDQ = 1, kBwdDKDV = 2 };
@@ -577,6 +581,107 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
           __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (DBIAS) dacc_add(stage, 1, dsf[1]);
+        done = true;
+      }
+    }
+    if constexpr (MODE == kBwdDKDV && C::kBf16 && NSB == 1 && D == 128 && C::kStatLds) {
+      // Software-pipelined dK/dV pass for fully visible 32-query tiles.  A matrix instruction hides vector instructions
+      // only when they follow it in the same wave, so the pointwise work rides behind this wave's own products:
+      //   slots  0..7   S  = Q K^T
+      //   slots  8..15  dP = dO V^T            | the part of the pointwise work that needs S only (sigmoid, P, dS/dP), as a
+      //   slots 16..19  dV^T += dO^T P, q 0..15  |   three-stage rolling chain (exp2; add, rcp; multiply-adds) over the 16
+      //   slots 20..23  dK^T += Q^T dS, q 0..15  |   score registers, finishing register 7 in slot 15 and register 15 in slot 23;
+      //   slots 24..27  dV^T, q 16..31           | dS = dP * (dS/dP) and its packing: q 0..15 in slots 17..19, q 16..31 in 24..27
+      //   slots 28..31  dK^T, q 16..31
+      // (score register r of a lane belongs to query 8 (r / 4) + 4 hf + r % 4: registers 0..7 are the queries of the
+      // first 16-row k-step of the output products.)
+      const bool tile_hist_f = min(y0 + C::BN, L) - 1 < g.n;               // candidate queries take the general path
+      if (kind == kTileFull && (!CANDK || tile_hist_f)) {
+        f32x16 sv, dp;
+        if (bias_h) {
+          const float* strip = (const float*)(smem + C::STRIP_BASE + stage * C::STRIP_BYTES) + strip_lane;
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x4 bv = *(const f32x4*)(strip + 8 * q4);
+            sv[4 * q4 + 0] = bv[0]; sv[4 * q4 + 1] = bv[1]; sv[4 * q4 + 2] = bv[2]; sv[4 * q4 + 3] = bv[3];
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sv[r] = 0.f;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+        auto statfrag = [&](int ks) -> bf16x8 {                           // V rows of this wave's keys: B operand of dP
+          return *(lds_b8)(uintptr_t)(uint32_t)(((kb - stage * C::STAGE_BYTES) ^ (ks << 5)) + C::STAT_BASE + wave * 8192);
+        };
+        // rolling pointwise chain over the score registers: E(r) exp2(-s); R(r) sigmoid; F(r) P (in place of s), dS/dP, packing of P
+        float ex[16], sg_[16], fac[16];
+        uint32_t pp[8], pds[8];
+        auto E_ = [&](int r) { ex[r] = __builtin_amdgcn_exp2f(-sv[r]); };
+        auto R_ = [&](int r) { sg_[r] = __builtin_amdgcn_rcpf(1.0f + ex[r]); };
+        auto F_ = [&](int r) {
+          const float pv = sv[r] * sg_[r];
+          fac[r] = dsilu_l2(pv, sg_[r]);
+          sv[r] = pv;
+          if (r & 1) { pp[r >> 1] = pack_bf16x2(sv[r - 1], sv[r]); asm volatile("" : "+v"(pp[r >> 1])); }
+        };
+        auto DS_ = [&](int m) {                                           // registers 2m, 2m + 1
+          pds[m] = pack_bf16x2(dp[2 * m] * fac[2 * m], dp[2 * m + 1] * fac[2 * m + 1]);
+          asm volatile("" : "+v"(pds[m]));
+        };
+        // what slot `sl` carries of the chain (register r: E in slot 6 + r, but not before slot 8; R one slot later; F two)
+        auto chain = [&](int sl) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int e_slot = r < 2 ? 8 : 6 + r;
+            if (sl == e_slot) E_(r);
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int e_slot = r < 2 ? 8 : 6 + r;
+            if (sl == e_slot + 1) R_(r);
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int e_slot = r < 2 ? 8 : 6 + r;
+            if (sl == e_slot + 2) F_(r);
+          }
+          if (sl == 17) { DS_(0); }
+          if (sl == 18) { DS_(1); DS_(2); }
+          if (sl == 19) { DS_(3); }
+          if (sl >= 24 && sl < 28) DS_(sl - 20);
+        };
+        constexpr int PF = HSTU_DKDV_PF;                                  // fragments are fetched PF slots ahead of their product
+        // A operand of slot n: Q rows (S), dO rows (dP), dO^T (dV), Q^T (dK)
+        auto afrag = [&](int n) -> bf16x8 {
+          if (n < 8) return rowfrag_at(0, 0, n);
+          if (n < 16) return rowfrag_at(1, 0, n - 8);
+          const int ks2 = (n - 16) >> 3, o = ((n - 16) >> 2) & 1, ob = n & 3;   // o = 0: dV (dO^T), 1: dK (Q^T)
+          return trfrag_at(o == 0 ? 1 : 0, 0, ks2, ob);
+        };
+        bf16x8 fr[PF], fv[PF];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) fr[i] = afrag(i);
+#pragma unroll
+        for (int n = 0; n < 32; ++n) {
+          const bf16x8 fa = fr[n % PF];
+          const bf16x8 fb = fv[n % PF];
+          if (n + PF < 32) fr[n % PF] = afrag(n + PF);
+          if (n + PF >= 8 && n + PF < 16) fv[n % PF] = statfrag(n + PF - 8);
+          if (n % (8 / C::CPT) == 0 && n < 8) gload_piece(n / (8 / C::CPT), stage ^ 1);
+          __builtin_amdgcn_sched_barrier(0);
+          if (n < 8) sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, res[0][n], sv, 0, 0, 0);
+          else if (n < 16) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, dp, 0, 0, 0);
+          else {
+            const int ks2 = (n - 16) >> 3, o = ((n - 16) >> 2) & 1, ob = n & 3;
+            const uint32_t* pk = (o == 0) ? pp : pds;
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){pk[4 * ks2], pk[4 * ks2 + 1], pk[4 * ks2 + 2], pk[4 * ks2 + 3]});
+            out[1 - o][ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, pb, out[1 - o][ob], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          chain(n);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         done = true;
       }
     }
