@@ -280,6 +280,56 @@ int hstu_norm_quant_fp8(int64_t T, int32_t D, int32_t dtype, const void* a, cons
 int hstu_fp8_gemm_bias2d(int64_t M, int32_t N, int32_t K, const void* a_q, const float* a_scale, const void* b_q,
                          const float* b_scale, const void* c, void* d, void* stream);
 
+/*
+ * Load-Balanced Stochastic Length (paper Section 4.1, "Load-Balanced Stochastic Length", and Alg. 1 of its appendix):
+ * the length sampler that keeps the attention load of the ranks of a data-parallel job level.  HOST code on HOST
+ * pointers: it deals in sequence lengths, never touches a GPU, and plays all `world_size` ranks in one process (the
+ * one number the ranks exchange, a mean load, is a plain mean here).  Load of a sequence of n items: n^gamma; load of a
+ * rank: the sum over its batch.
+ *
+ * Stochastic Length with sampling length sl_len (= L^(alpha/2) in the paper's notation): a sequence of n <= sl_len items
+ * is left alone; a longer one stays whole with probability hstu_lbsl_weight(n) = (sl_len / n)^2 and is cut to sl_len
+ * items otherwise.  hstu_lbsl_expected_load(n) = w n^gamma + (1 - w) min(n, sl_len)^gamma is the load it leaves on
+ * average.
+ *
+ * hstu_lbsl_step runs one training step of Alg. 1 for every rank.  rank_offsets [world_size + 1] (starting at 0,
+ * non-decreasing) delimits the ranks' batches inside lengths [total] (raw lengths >= 0) and uniforms [total] (one number
+ * in (0, 1] per sequence, drawn by the caller).  Every rank first adds the expected plain-SL load of its batch to
+ * state.rank_load[r].  During the first warmup_steps steps it then applies plain SL (sequence u stays whole iff
+ * uniforms[u] < weight).  Afterwards it visits its batch in a weighted random order without replacement (weights = the
+ * weights above, drawn with exponential clocks: ascending -ln(uniforms[u]) / weight, ties by index) and leaves u whole
+ * while the load so added, n^gamma - min(n, sl_len)^gamma each, stays within state.target minus the load of the batch
+ * with every long sequence cut; the rest is cut to sl_len.  Outputs: new_lengths [total], unsampled [total] (1 = left
+ * whole), realised_load [world_size] (sum of new_length^gamma; may be NULL).  At the end of step warmup_steps the target
+ * becomes the mean of rank_load over ranks and warm-up steps and the accumulators restart; after the warm-up the same
+ * happens at every step that is a multiple of recal_interval (mean over ranks and recal_interval steps).
+ * hstu_lbsl_init clears a state whose rank_load the caller has pointed at world_size doubles.
+ * Errors: HSTU_ERR_NULL, HSTU_ERR_SHAPE (world_size, warmup_steps, recal_interval, sl_len < 1, gamma not positive and
+ * finite, offsets not as described, a negative length, a uniform outside (0, 1]); nothing is written then.  The step
+ * allocates host memory for its sort; not thread-safe per state.
+ *
+ * hstu_lbsl_fit_gamma: the exponent that a measured cost curve implies, the least-squares slope of log(times[i]) against
+ * log(lengths[i]) over n >= 2 points (all > 0, at least two distinct lengths).
+ */
+typedef struct hstu_lbsl_config {
+  int32_t world_size;      /* R */
+  int32_t warmup_steps;    /* T_warm */
+  int32_t recal_interval;  /* T_recal */
+  int32_t sl_len;          /* l_SL */
+  double gamma;            /* load exponent */
+} hstu_lbsl_config;
+typedef struct hstu_lbsl_state {
+  int64_t step;            /* steps done so far */
+  double target;           /* the target load; 0 until the warm-up ends */
+  double* rank_load;       /* HOST double[world_size], owned by the caller: the accumulators l_r */
+} hstu_lbsl_state;
+double hstu_lbsl_weight(int32_t n, int32_t sl_len);
+double hstu_lbsl_expected_load(int32_t n, int32_t sl_len, double gamma);
+int hstu_lbsl_init(const hstu_lbsl_config* cfg, hstu_lbsl_state* state);
+int hstu_lbsl_step(const hstu_lbsl_config* cfg, hstu_lbsl_state* state, const int32_t* rank_offsets, const int32_t* lengths,
+                   const double* uniforms, int32_t* new_lengths, uint8_t* unsampled, double* realised_load);
+int hstu_lbsl_fit_gamma(int32_t n, const double* lengths, const double* times, double* gamma);
+
 /* Human-readable name of a status code (static storage). */
 const char* hstu_status_string(int status);
 

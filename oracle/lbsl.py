@@ -24,6 +24,9 @@ What the paper fixes and what is a reading of it:
     gets a negative budget, admits nobody and lands far below the target, against the text's "matches l as closely as
     possible".  So the sampled weight of a sequence is min(n_u, l_SL)^gamma here: the baseline is the sum of those, and
     admitting u costs n_u^gamma - min(n_u, l_SL)^gamma.  When every n_u >= l_SL this is the listing's condition verbatim.
+  * READING: the periodic recalibration runs after the warm-up only.  The listing's "else if t mod T_recal = 0" would
+    also fire inside a warm-up longer than T_recal and clear the accumulators that the warm-up mean (divided by T_warm)
+    is about to use.
   * The first window after warm-up may hold fewer than T_recal steps; the listing divides by T_recal all the same, and so
     does this.
 """
@@ -110,7 +113,7 @@ class Lbsl:
         if t == self.t_warm:
             self.target = sum(self.rank_load) / (self.R * self.t_warm)
             self.rank_load = [0.0] * self.R
-        elif t % self.t_recal == 0:
+        elif t > self.t_warm and t % self.t_recal == 0:
             self.target = sum(self.rank_load) / (self.R * self.t_recal)
             self.rank_load = [0.0] * self.R
         return out_len, out_keep, realised

@@ -50,6 +50,15 @@ class HstuLayerParams(ctypes.Structure):
     ]
 
 
+class HstuLbslConfig(ctypes.Structure):
+    _fields_ = [("world_size", ctypes.c_int32), ("warmup_steps", ctypes.c_int32), ("recal_interval", ctypes.c_int32),
+                ("sl_len", ctypes.c_int32), ("gamma", ctypes.c_double)]
+
+
+class HstuLbslState(ctypes.Structure):
+    _fields_ = [("step", ctypes.c_int64), ("target", ctypes.c_double), ("rank_load", ctypes.c_void_p)]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2602_16986_amd.build` "
@@ -96,6 +105,17 @@ def _load() -> ctypes.CDLL:
     lib.hstu_norm_quant_fp8.argtypes = [i64, i32, i32, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
     lib.hstu_fp8_gemm_bias2d.restype = ctypes.c_int
     lib.hstu_fp8_gemm_bias2d.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    cp, sp = ctypes.POINTER(HstuLbslConfig), ctypes.POINTER(HstuLbslState)
+    lib.hstu_lbsl_weight.restype = ctypes.c_double
+    lib.hstu_lbsl_weight.argtypes = [i32, i32]
+    lib.hstu_lbsl_expected_load.restype = ctypes.c_double
+    lib.hstu_lbsl_expected_load.argtypes = [i32, i32, ctypes.c_double]
+    lib.hstu_lbsl_init.restype = ctypes.c_int
+    lib.hstu_lbsl_init.argtypes = [cp, sp]
+    lib.hstu_lbsl_step.restype = ctypes.c_int
+    lib.hstu_lbsl_step.argtypes = [cp, sp, vp, vp, vp, vp, vp, vp]
+    lib.hstu_lbsl_fit_gamma.restype = ctypes.c_int
+    lib.hstu_lbsl_fit_gamma.argtypes = [i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.hstu_profile_enable.restype = ctypes.c_int
     lib.hstu_profile_enable.argtypes = [ctypes.c_int]
     lib.hstu_profile_read.restype = ctypes.c_int
@@ -110,7 +130,8 @@ EXPORTS = ["hstu_attn_workspace_bytes", "hstu_attn_fwd", "hstu_attn_bwd", "hstu_
            "hstu_attn_schedule_stats", "hstu_profile_enable", "hstu_profile_read",
            "hstu_truncate_offsets", "hstu_truncate_fwd", "hstu_truncate_bwd",
            "hstu_layer_workspace_bytes", "hstu_layer_fwd", "hstu_layer_bwd", "hstu_layer_gemm_tunings",
-           "hstu_norm_quant_fp8", "hstu_fp8_gemm_bias2d"]
+           "hstu_norm_quant_fp8", "hstu_fp8_gemm_bias2d",
+           "hstu_lbsl_weight", "hstu_lbsl_expected_load", "hstu_lbsl_init", "hstu_lbsl_step", "hstu_lbsl_fit_gamma"]
 
 
 def status_string(status: int) -> str:
@@ -333,6 +354,60 @@ def hstu_layer_bwd(prob: LayerProblem, z, u_saved, attn_saved, mean, rstd, dout,
 def hstu_layer_gemm_tunings() -> int:
     """How many times the layer's GEMMs have timed candidate kernels (and blocked the host) in this process."""
     return int(_lib.hstu_layer_gemm_tunings())
+
+
+def hstu_lbsl_weight(n: int, sl_len: int) -> float:
+    return float(_lib.hstu_lbsl_weight(int(n), int(sl_len)))
+
+
+def hstu_lbsl_expected_load(n: int, sl_len: int, gamma: float) -> float:
+    return float(_lib.hstu_lbsl_expected_load(int(n), int(sl_len), float(gamma)))
+
+
+class Lbsl:
+    """Load-Balanced Stochastic Length over simulated ranks (hstu_lbsl_init / hstu_lbsl_step); host arrays are numpy."""
+
+    def __init__(self, world_size: int, warmup_steps: int, recal_interval: int, sl_len: int, gamma: float):
+        self.cfg = HstuLbslConfig(int(world_size), int(warmup_steps), int(recal_interval), int(sl_len), float(gamma))
+        self.rank_load = np.zeros(max(int(world_size), 1), dtype=np.float64)
+        self.state = HstuLbslState(0, 0.0, self.rank_load.ctypes.data)
+        st = _lib.hstu_lbsl_init(ctypes.byref(self.cfg), ctypes.byref(self.state))
+        if st != HSTU_OK:
+            raise HstuError(st, "hstu_lbsl_init")
+
+    @property
+    def target(self) -> float:
+        return float(self.state.target)
+
+    @property
+    def step_no(self) -> int:
+        return int(self.state.step)
+
+    def step(self, rank_offsets, lengths, uniforms):
+        """One step for every rank.  Returns (new_lengths int32[total], unsampled uint8[total], realised_load float64[R])."""
+        off = np.ascontiguousarray(rank_offsets, dtype=np.int32)
+        lens = np.ascontiguousarray(lengths, dtype=np.int32)
+        us = np.ascontiguousarray(uniforms, dtype=np.float64)
+        if off.shape[0] != self.cfg.world_size + 1 or lens.shape != us.shape or (off.size and int(off[-1]) != lens.shape[0]):
+            raise HstuError(-2, "hstu_lbsl_step (array shapes)")
+        new = np.empty_like(lens)
+        keep = np.empty(lens.shape[0], dtype=np.uint8)
+        real = np.empty(self.cfg.world_size, dtype=np.float64)
+        st = _lib.hstu_lbsl_step(ctypes.byref(self.cfg), ctypes.byref(self.state), off.ctypes.data, lens.ctypes.data, us.ctypes.data,
+                                 new.ctypes.data, keep.ctypes.data, real.ctypes.data)
+        if st != HSTU_OK:
+            raise HstuError(st, "hstu_lbsl_step")
+        return new, keep, real
+
+
+def hstu_lbsl_fit_gamma(lengths, times) -> float:
+    ls = np.ascontiguousarray(lengths, dtype=np.float64)
+    ts = np.ascontiguousarray(times, dtype=np.float64)
+    out = ctypes.c_double(0.0)
+    st = _lib.hstu_lbsl_fit_gamma(int(ls.shape[0]), ls.ctypes.data, ts.ctypes.data, ctypes.byref(out))
+    if st != HSTU_OK or ls.shape != ts.shape:
+        raise HstuError(st if st != HSTU_OK else -2, "hstu_lbsl_fit_gamma")
+    return float(out.value)
 
 
 def hstu_norm_quant_fp8(a, u, gamma, beta, eps, q, q_scale, mean=None, rstd=None, stream=None) -> None:

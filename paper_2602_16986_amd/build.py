@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhstu_attn.so")
-SOURCES = ["api.hip", "schedule.hip", "attn_core.hip", "attn_fwd_pipe.hip", "gated_norm.hip", "truncate.hip", "pointwise.hip", "gemm.hip", "gemm_tn.hip", "layer.hip", "fp8_gemm.hip"]
+SOURCES = ["api.hip", "schedule.hip", "attn_core.hip", "attn_fwd_pipe.hip", "gated_norm.hip", "truncate.hip", "pointwise.hip", "gemm.hip", "gemm_tn.hip", "layer.hip", "fp8_gemm.hip", "lbsl.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          # packed fp32 VALU forms are kept off on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
