@@ -21,7 +21,7 @@ namespace hstu {
 namespace {
 
 struct Shape {
-  int device, op; int64_t M, N, K, lda, ldb, ldc, ldd; bool residual, d_fp32;
+  int device, op; int64_t M, N, K, lda, ldb, ldc, ldd; bool residual, d_fp32, silu;
 };
 struct Plan {
   Shape s;
@@ -54,7 +54,7 @@ Shape class_of(Shape s) {
 }
 bool same(const Shape& a, const Shape& b) {
   return a.device == b.device && a.op == b.op && a.M == b.M && a.N == b.N && a.K == b.K && a.lda == b.lda && a.ldb == b.ldb &&
-         a.ldd == b.ldd && a.residual == b.residual && (!a.residual || a.ldc == b.ldc) && a.d_fp32 == b.d_fp32;
+         a.ldd == b.ldd && a.residual == b.residual && (!a.residual || a.ldc == b.ldc) && a.d_fp32 == b.d_fp32 && a.silu == b.silu;
 }
 void destroy(Plan& pl) {
   if (pl.desc) hipblasLtMatmulDescDestroy(pl.desc);
@@ -78,8 +78,10 @@ bool describe(Plan& pl) {
     ta = HIPBLAS_OP_N; tb = HIPBLAS_OP_T; a_rows = s.N; a_cols = s.K; b_rows = s.M; b_cols = s.K;
   }
   const hipDataType dt = s.d_fp32 ? HIP_R_32F : HIP_R_16BF;
+  const hipblasLtEpilogue_t epi = s.silu ? HIPBLASLT_EPILOGUE_SWISH_EXT : HIPBLASLT_EPILOGUE_DEFAULT;   // Swish(x, 1) = x sigmoid(x) = SiLU
   const bool ok =
       hipblasLtMatmulDescCreate(&pl.desc, HIPBLAS_COMPUTE_32F, HIP_R_32F) == HIPBLAS_STATUS_SUCCESS &&
+      hipblasLtMatmulDescSetAttribute(pl.desc, HIPBLASLT_MATMUL_DESC_EPILOGUE, &epi, sizeof(epi)) == HIPBLAS_STATUS_SUCCESS &&
       hipblasLtMatmulDescSetAttribute(pl.desc, HIPBLASLT_MATMUL_DESC_TRANSA, &ta, sizeof(ta)) == HIPBLAS_STATUS_SUCCESS &&
       hipblasLtMatmulDescSetAttribute(pl.desc, HIPBLASLT_MATMUL_DESC_TRANSB, &tb, sizeof(tb)) == HIPBLAS_STATUS_SUCCESS &&
       hipblasLtMatrixLayoutCreate(&pl.la, HIP_R_16BF, a_rows, a_cols, s.ldb) == HIPBLAS_STATUS_SUCCESS &&
@@ -181,7 +183,7 @@ int choose_algo(Plan& pl, const void* A, const void* B, const void* C, void* D, 
 long gemm_bf16_tunings() { return g_tunings; }
 
 int gemm_bf16(int op, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, const void* C,
-              int64_t ldc, void* D, int64_t ldd, bool d_fp32, void* ws, size_t ws_bytes, hipStream_t stream) {
+              int64_t ldc, void* D, int64_t ldd, bool d_fp32, void* ws, size_t ws_bytes, hipStream_t stream, bool silu) {
   if (M <= 0 || N <= 0 || K <= 0) return -1;
   int device = 0;
   if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return -1;
@@ -190,7 +192,7 @@ int gemm_bf16(int op, int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
     g_has_handle[device] = true;
   }
   const bool residual = C != nullptr;
-  const Shape shape = {device, op, M, N, K, lda, ldb, ldc, ldd, residual, d_fp32};
+  const Shape shape = {device, op, M, N, K, lda, ldb, ldc, ldd, residual, d_fp32, silu};
   Plan* pl = nullptr;
   for (int i = 0; i < g_nplans; ++i)
     if (same(g_plans[i].s, shape) && g_plans[i].ws_needed <= ws_bytes) { pl = &g_plans[i]; break; }

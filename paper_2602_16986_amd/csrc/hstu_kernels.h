@@ -142,11 +142,12 @@ hipError_t launch_silu_bwd(int64_t T, int C, const void* pre, void* dact, hipStr
 // gemm.hip: row-major bf16 products with fp32 accumulation through hipBLASLt.
 //   kGemmNT: D[M,N] = A[M,K] B[N,K]^T    kGemmNN: D[M,N] = A[M,K] B[K,N]    kGemmTN: D[M,N] = A[K,M]^T B[K,N]
 // C: optional bf16 [M,N] added to the product (nullptr: none); D bf16 or fp32 (d_fp32); ld*: row strides in elements.
+// silu: SiLU applied to the product in the library's epilogue, before the one rounding to bf16.
 // Returns 0, -1 (library error) or -2 (no kernel for this problem).  gemm_bf16_tunings: how often candidates were timed.
 enum { kGemmNT = 0, kGemmNN = 1, kGemmTN = 2 };
 long gemm_bf16_tunings();
 int gemm_bf16(int op, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, const void* C,
-              int64_t ldc, void* D, int64_t ldd, bool d_fp32, void* ws, size_t ws_bytes, hipStream_t stream);
+              int64_t ldc, void* D, int64_t ldd, bool d_fp32, void* ws, size_t ws_bytes, hipStream_t stream, bool silu = false);
 
 // fp8_gemm.hip: D[M,N] (bf16) = a_scale[m] b_scale[n] (Aq[M,K] Bq[N,K]^T) + C[M,N] (bf16 or nullptr), E4M3 codes
 bool fp8_gemm_supported(int N, int K);

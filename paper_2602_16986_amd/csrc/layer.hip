@@ -130,14 +130,25 @@ int hstu_layer_fwd(const hstu_layer_params* p, const void* z, void* out, void* u
     ProfScope ps("fp8_gemm_uvqk", stream);
     if (launch_fp8_gemm_silu(T, (int)(4 * HD), (int)E, xn, xscale, p->w1_q, p->w1_scale, act, u_saved, (int)HD, stream) != hipSuccess)
       return HSTU_ERR_LAUNCH;
-  } else {  // Eq. 2: [U V Q K] = SiLU(X W1^T)
-    ProfScope ps("gemm_uvqk", stream);
-    st = gemm_status(gemm_bf16(kGemmNT, T, 4 * HD, E, xn, E, p->w1, E, nullptr, 0, act, 4 * HD, false, ws + l.gemm, kGemmWorkspace, stream));
-    if (st != HSTU_OK) return st;
-  }
-  if (!fp8) {
-    ProfScope ps("silu_fwd", stream);
-    if (launch_silu_fwd(T, (int)(4 * HD), act, act, u_saved, (int)HD, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  } else {
+    // Eq. 2: [U V Q K] = SiLU(X W1^T), SiLU in the GEMM library's epilogue: the gate's rows of W1 go straight to the saved-U
+    // tensor, the V, Q, K rows to their column blocks of the projection buffer.  A library build without such a kernel
+    // (-2) gets the plain product and a SiLU pass.
+    bool fused;
+    {
+      ProfScope ps("gemm_uvqk", stream);
+      int rc = gemm_bf16(kGemmNT, T, HD, E, xn, E, p->w1, E, nullptr, 0, u_saved, HD, false, ws + l.gemm, kGemmWorkspace, stream, true);
+      if (rc == 0)
+        rc = gemm_bf16(kGemmNT, T, 3 * HD, E, xn, E, (const __bf16*)p->w1 + HD * E, E, nullptr, 0, act + HD, 4 * HD, false, ws + l.gemm,
+                       kGemmWorkspace, stream, true);
+      fused = rc == 0;
+      if (rc == -2) rc = gemm_bf16(kGemmNT, T, 4 * HD, E, xn, E, p->w1, E, nullptr, 0, act, 4 * HD, false, ws + l.gemm, kGemmWorkspace, stream);
+      if (rc != 0) return gemm_status(rc);
+    }
+    if (!fused) {
+      ProfScope ps("silu_fwd", stream);
+      if (launch_silu_fwd(T, (int)(4 * HD), act, act, u_saved, (int)HD, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    }
   }
   // Eq. 3: A = attention(Q, K, V) on column blocks of the projection buffer
   st = hstu_attn_fwd(&ap, act + 2 * HD, act + 3 * HD, act + HD, attn_saved, ws + l.attn, l.attn_bytes, stream_);
