@@ -319,6 +319,10 @@ def layer_case(name: str, seed: int = 0) -> LayerCase:
     if name == "layer-mid":
         L = np.random.default_rng(seed + 1).integers(1024, 2049, size=4)
         return build_layer(name, L, 4, 128, 512, seed=seed)
+    if name == "layer-long":      # sequences of the benchmark's length range, as many as the oracle affords
+        return build_layer(name, [8192, 4200], 4, 128, 512, seed=seed)
+    if name == "layer-long-sparse":
+        return build_layer(name, [8192, 4200], 4, 128, 512, seed=seed, K1=1024, K2=256)
     if name == "layer-small-dense":
         return build_layer(name, [70, 0, 33, 129], 2, 64, 96, seed=seed)
     if name == "layer-small-sparse-targets":

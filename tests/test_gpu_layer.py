@@ -85,6 +85,14 @@ def test_layer_mid(hb):
     run_case(wl.layer_case("layer-mid"))
 
 
+@pytest.mark.parametrize("name", ["layer-long", "layer-long-sparse"])
+def test_layer_long_sequences_against_the_oracle(hb, name):
+    """Two sequences of 8,192 and 4,200 tokens (the first inside the benchmark's length range; 64 and 33 row blocks, cut and
+    uncut work items, the pipelined kernels' long tile lists), H=4, d=128, E=512: forward and every gradient of the whole
+    layer against the fp64 oracle, dense and under the semi-local mask."""
+    run_case(wl.layer_case(name))
+
+
 def test_layer_backward_twice_is_identical(hb):
     """The backward rebuilds its intermediates from (Z, U, A, statistics) alone: a second call after unrelated work in
     the same workspace returns bit-identical gradients (attention and norms are deterministic, the GEMM plans are fixed)."""
