@@ -70,8 +70,8 @@ Layout make_layout(const hstu_attn_params* p, int for_backward) {
     l.splits_dq = off; off += align_up((size_t)(l.slot_cap_dq / 2 + 1) * sizeof(SplitItem));
     l.partial_dq = off;
     off += align_up((size_t)l.slot_cap_dq * dq_block_rows(p->dtype, p->head_dim) * p->head_dim * sizeof(float));
-    l.dbias = off;                                     // per-distance sums of dS for the bias-table gradient
-    off += align_up((size_t)p->num_heads * ((size_t)p->max_seqlen + 1) * sizeof(float));
+    l.dbias = off;                                     // per-distance sums of dS for the bias-table gradient, then the bucket ends per distance
+    off += align_up((size_t)(p->num_heads + 1) * ((size_t)p->max_seqlen + 1) * sizeof(float));
   }
   l.total = off;
   return l;
@@ -145,7 +145,10 @@ hipError_t prepare_bias(const hstu_attn_params* p, AttnArgs& a, unsigned char* w
   if (!p->rab_table) return hipSuccess;
   float* bias = (float*)(ws + l.bias);
   a.bias = bias;
-  return launch_bias_expand(p->rab_table, p->rab_bounds, p->num_buckets, p->num_heads, a.bias_stride, bias, stream);
+  int32_t* bucket_end = nullptr;                      // only the bias-table gradient needs the bucket ends
+  if (!for_forward && p->d_rab_table) bucket_end = (int32_t*)(ws + l.dbias) + (size_t)p->num_heads * a.bias_stride;
+  a.bucket_end = bucket_end;
+  return launch_bias_expand(p->rab_table, p->rab_bounds, p->num_buckets, p->num_heads, a.bias_stride, bias, bucket_end, stream);
 }
 
 }  // namespace

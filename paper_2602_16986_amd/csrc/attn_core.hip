@@ -409,6 +409,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     // (different half-waves, different classes), so the half-waves and the classes take turns.
     float* base = dacc + stage * C::DACC_COPIES * C::DACC_LEN + dacc_lane + sub * 32;
     const int room = C::DACC_LEN - (dacc_lane - wave * C::DACC_LEN + sub * 32);   // entries from base to the end of the strip
+    // (lanes of the two 16-lane rows of a half-wave meet in neighbouring classes, so the classes take turns as well)
 #pragma unroll
     for (int hs = 0; hs < 2; ++hs)
 #pragma unroll
@@ -419,6 +420,55 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
           *p = *p + xv;
         }
       }
+  };
+  // A tile that lies far from the diagonal has all its distances inside ONE bucket of the table, or in two neighbouring
+  // ones (the buckets of a log-spaced table are hundreds of distances wide there); which distance of a bucket receives a
+  // sum does not matter, so such a tile adds plain sums of its dS: one per bucket, kept per lane across consecutive tiles
+  // (two open buckets, since the tiles walk from one bucket into the next) and reduced over the wave only when a bucket
+  // is left behind.  The test is made for the whole block (its 128 rows against the tile's keys: AttnArgs::bucket_end
+  // gives the first distance of the next bucket), so that all waves agree and the per-tile flush of the diagonal strips
+  // can be skipped too.
+  float run_sum0 = 0.f, run_sum1 = 0.f;
+  int run_end0 = 0, run_end1 = 0, run_dist0 = 0, run_dist1 = 0;          // run_end = 0: slot free; a bucket is named by its end
+  int run_old = 0;                                                        // the slot opened first
+  auto run_flush_slot = [&](float& sum, int& end, int dist) {
+    if (end != 0) {
+      float v = sum;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+      if (lane == 0 && v != 0.f) atomicAdd(a.dbias_dist + (int64_t)h * a.bias_stride + dist, v);
+      sum = 0.f;
+      end = 0;
+    }
+  };
+  auto run_flush = [&]() {
+    if constexpr (DBIAS) { run_flush_slot(run_sum0, run_end0, run_dist0); run_flush_slot(run_sum1, run_end1, run_dist1); }
+  };
+  auto run_to = [&](int end, int dist, float v) {                        // adds v to the bucket that ends at `end` (dist: one of its distances)
+    if (run_end0 == end) run_sum0 += v;
+    else if (run_end1 == end) run_sum1 += v;
+    else if (run_old == 0) {
+      run_flush_slot(run_sum0, run_end0, run_dist0);
+      run_end0 = end; run_dist0 = dist; run_sum0 = v; run_old = 1;
+    } else {
+      run_flush_slot(run_sum1, run_end1, run_dist1);
+      run_end1 = end; run_dist1 = dist; run_sum1 = v; run_old = 0;
+    }
+  };
+  // vals: the 16 dS of this lane in sub-block `sub` of the tile (keys y0 + 32 sub + 8 (r / 4) + 4 hf + r % 4).  The block's
+  // pairs of this tile lie in the bucket that ends at `end` (distances < end) and, if split >= 0, above it in the bucket
+  // that ends at `end2`.
+  auto run_add = [&](const float* vals, int sub, int y0_, int end, int dist, int end2) {
+    float total = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) total += vals[r];
+    if (end2 == 0) { run_to(end, dist, total); return; }
+    const int thr = x - y0_ - 32 * sub - 4 * hf - end;                   // key offset c <= thr  <=>  distance >= end
+    float hi = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) hi += (8 * (r >> 2) + (r & 3) <= thr) ? vals[r] : 0.f;
+    run_to(end, dist, total - hi);
+    run_to(end2, end, hi);
   };
   if constexpr (DBIAS) {
     for (int i = tid; i < 2 * C::DACC_COPIES * C::DACC_LEN; i += C::NT) dacc[i] = 0.f;
@@ -431,17 +481,33 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   const bool stat_hist = min(xw0 + 32, L) - 1 < g.n;  // this wave's stationary rows are all history rows
   constexpr int NSB = C::BN / 32;                     // 32-row sub-blocks of a streamed tile
   constexpr int SBG = (MODE == kFwd && NSB >= 2) ? 2 : 1;   // sub-blocks whose products are interleaved
+  bool prev_fast = false;
   for (int t = t_begin; t < ntiles; ++t) {
     const int yt = nx_yt;                                    // set_next() of the previous round (or of the prologue) named this tile
     const int stage = (t - t_begin) & 1;
     const bool has_next = t + 1 < ntiles;
     set_next(has_next ? tr.at(t + 1) : 0, has_next);
     if constexpr (DBIAS) {
-      if (t > t_begin) dacc_flush(stage ^ 1, tr.at(t - 1));
+      if (t > t_begin && !prev_fast) dacc_flush(stage ^ 1, tr.at(t - 1));
     }
     const unsigned char* y1s = smem + stage * C::STAGE_BYTES;
     const unsigned char* y2s = y1s + C::TILE0;
     const int y0 = yt * C::BN;
+    bool wg_fast = false;                                                 // DBIAS: the whole block's pairs of this tile lie in one or two buckets
+    int fast_end = 0, fast_dist = 0, fast_end2 = 0;
+    if constexpr (DBIAS) {
+      const int xhi = x0 + C::BX - 1, dmin_b = x0 - (y0 + C::BN - 1);
+      if (a.bucket_end && a.dbias_dist && dmin_b >= 0 && xhi < g.n && classify_tile(g, x0, xhi, y0, y0 + C::BN - 1, false) == kTileFull) {
+        fast_end = a.bucket_end[dmin_b];
+        fast_dist = dmin_b;
+        wg_fast = true;
+        if (fast_end <= xhi - y0) {                                       // a bucket boundary inside the tile's distances
+          fast_end2 = a.bucket_end[fast_end];
+          wg_fast = fast_end2 > xhi - y0;                                 // ... and only one
+        }
+      }
+      prev_fast = wg_fast;
+    }
 
     // How this wave's 32 stationary rows relate to the tile: nothing visible (skip), everything
     // visible (no mask arithmetic, bias from the strip), or mixed (generic per-element path).
@@ -563,7 +629,9 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
           if (n >= 16 && (n & 1)) pointwise(0, (n - 16) >> 1);
           __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (DBIAS) dacc_add(stage, 0, dsf[0]);                  // fully visible tile: history rows, distance x - y
+        if constexpr (DBIAS) {                                            // fully visible tile: history rows, distance x - y
+          if (wg_fast) run_add(dsf[0], 0, y0, fast_end, fast_dist, fast_end2); else dacc_add(stage, 0, dsf[0]);
+        }
         constexpr int NO = 16 * C::NOUT;                                  // output products of the tile
 #pragma unroll
         for (int i = 0; i < PF; ++i) fr[i] = trfrag(i);
@@ -580,7 +648,9 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
           if (sb == 0 && o == C::NOUT - 1) pointwise(1, step);
           __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (DBIAS) dacc_add(stage, 1, dsf[1]);
+        if constexpr (DBIAS) {
+          if (wg_fast) run_add(dsf[1], 1, y0, fast_end, fast_dist, fast_end2); else dacc_add(stage, 1, dsf[1]);
+        }
         done = true;
       }
     }
@@ -910,7 +980,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
                   atomicAdd(a.dbias_dist + (int64_t)h * a.bias_stride + delta, c1[u][r]);
               }
             }
-            dacc_add(stage, sg + u, hv);
+            if (wg_fast) run_add(hv, sg + u, y0, fast_end, fast_dist, fast_end2); else dacc_add(stage, sg + u, hv);
           }
         }
 
@@ -978,7 +1048,8 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   }
 
   if constexpr (DBIAS) {
-    if (ntiles > t_begin) dacc_flush((ntiles - 1 - t_begin) & 1, tr.at(ntiles - 1));
+    if (ntiles > t_begin && !prev_fast) dacc_flush((ntiles - 1 - t_begin) & 1, tr.at(ntiles - 1));
+    run_flush();
   }
   // ---- epilogue: scale once, convert, store.  Lane x holds features ob*32 + 8*(r/4) + 4*hf + r%4.
   {

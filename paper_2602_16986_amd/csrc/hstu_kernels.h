@@ -47,6 +47,7 @@ struct AttnArgs {
   const SplitItem* splits;
   int32_t query_tail;               // forward only, > 0: compute only the last query_tail history rows and the candidates of every sequence
   float* dbias_dist;                // dQ pass, optional: sum of dS per head and distance [H, bias_stride] (zeroed by the caller)
+  const int32_t* bucket_end;        // with dbias_dist: [bias_stride], the first distance of the bucket after the one that holds distance i (INT_MAX: none)
   // Score seeds of the pipelined kernels: bias and mask of a (position, key) pair as a function of the distance
   // d = position - key alone, [variant][H][seed_len] floats:  seed[i] <-> d = seed_dmax - i (descending distances, so that
   // 4 consecutive floats are the seeds of 4 consecutive keys).  d < 0 (a later key): -1e30 (which the pointwise step
@@ -70,7 +71,8 @@ hipError_t launch_schedule(const AttnArgs& a, int block_rows, int tile_cols, boo
 hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], const int tile_cols[2], SchedHeader* const header[2],
                                 WorkItem* const items[2], int32_t* const seq_base[2], SplitItem* const splits[2],
                                 const int slot_cap[2], hipStream_t stream);
-hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
+// bucket_end (optional, [len]): for every distance the first distance of the next bucket
+hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out, int32_t* bucket_end,
                               hipStream_t stream);
 // fills AttnArgs::seed (table may be nullptr: no bias)
 hipError_t launch_seed_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int max_seqlen, int K1,

@@ -347,7 +347,7 @@ hipError_t launch_schedule_pair(const AttnArgs& a, const int block_rows[2], cons
 // the attention kernels keep their scores in units of ln 2.
 __global__ __launch_bounds__(256) void bias_expand_kernel(const float* __restrict__ table,
                                                           const int32_t* __restrict__ bounds, int nb, int H, int len,
-                                                          float* __restrict__ out) {
+                                                          float* __restrict__ out, int32_t* __restrict__ bucket_end) {
   const int x = blockIdx.x * blockDim.x + threadIdx.x;
   if (x >= len) return;
   int lo = 0, hi = nb;                                   // bounds[lo] <= x < bounds[hi] (bounds[nb] = +inf)
@@ -356,6 +356,7 @@ __global__ __launch_bounds__(256) void bias_expand_kernel(const float* __restric
     if (bounds[mid] <= x) lo = mid; else hi = mid;
   }
   for (int h = 0; h < H; ++h) out[(size_t)h * len + x] = table[(size_t)h * nb + lo] * 1.4426950408889634f;
+  if (bucket_end) bucket_end[x] = hi < nb ? bounds[hi] : 0x7FFFFFFF;
 }
 
 // Score seeds by distance (AttnArgs::seed): out[v][h][i], d = dmax - i.
@@ -390,9 +391,9 @@ hipError_t launch_seed_expand(const float* table, const int32_t* bounds, int num
 }
 
 hipError_t launch_bias_expand(const float* table, const int32_t* bounds, int num_buckets, int H, int len, float* out,
-                              hipStream_t stream) {
+                              int32_t* bucket_end, hipStream_t stream) {
   hipLaunchKernelGGL(bias_expand_kernel, dim3((len + 255) / 256), dim3(256), 0, stream, table, bounds, num_buckets, H,
-                     len, out);
+                     len, out, bucket_end);
   return hipGetLastError();
 }
 

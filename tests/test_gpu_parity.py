@@ -233,6 +233,16 @@ def test_bias_table_gradient_general_alpha_and_targets(hb):
     bias_gradient_case(w)
 
 
+def test_bias_table_gradient_long_sequences(hb):
+    """Sequences long enough that whole 128 x 64 tiles fall inside one bucket of the log-spaced table (distances beyond about
+    2,200): those tiles add a plain sum instead of diagonal sums.  bf16 / 128 features (pipelined tiles), and fp32 / 32
+    features (general path), dense and with a local window wider than the single-bucket distance."""
+    rng = np.random.default_rng(92)
+    bias_gradient_case(wl.build("dbias-long", [6000, 3100], 2, 128, "bf16", rng=rng, backward=True))
+    bias_gradient_case(wl.build("dbias-long-window", [7000], 1, 128, "bf16", rng=rng, K1=4000, K2=300, backward=True))
+    bias_gradient_case(wl.build("dbias-long-fp32", [4200], 1, 32, "fp32", rng=rng, backward=True))
+
+
 # ----------------------------------------------------------------------------------------------
 # forward restricted to the last rows of every sequence (hstu_attn_params.query_tail)
 # ----------------------------------------------------------------------------------------------
