@@ -218,14 +218,23 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
   __bf16* dxn = (__bf16*)(ws + l.dxn);
   float* partial = (float*)(ws + l.norm_partial);
   void* gws = ws + l.gemm;
-  {  // rematerialise Y from the saved A and U
-    ProfScope ps("gated_norm_fwd", stream);
-    if (launch_gated_norm_fwd(T, (int)HD, HSTU_BF16, attn_saved, u_saved, p->gated_norm_w, nullptr, p->gated_norm_eps, y, nullptr, nullptr,
-                              stream) != hipSuccess)
-      return HSTU_ERR_LAUNCH;
-  }
   const bool fp8 = p->w1_q != nullptr;
-  {  // rematerialise the normalised input from the saved statistics (in bf16: the weight gradient needs it in any case)
+  // Ordered by what each step needs, not by the forward's order: the gradient of the output projection and the gated norm's
+  // backward need only dout and the saved tensors, so they go first; Y is rebuilt last, right before the one product that reads it.
+  {  // Eq. 5 / f2, out = Y W2^T + Z:  dY = dout W2
+    ProfScope ps("gemm_dy", stream);
+    st = gemm_status(gemm_bf16(kGemmNN, T, HD, E, dout, E, p->w2, HD, nullptr, 0, dy, HD, false, gws, kGemmWorkspace, stream));
+    if (st != HSTU_OK) return st;
+  }
+  {  // Eq. 4 backward: dA, dU (straight into the U block of the projection gradient), d gated_norm_w
+    ProfScope ps("gated_norm_bwd", stream);
+    NormBwdArgs n = {};
+    n.T = T; n.D = (int32_t)HD; n.dtype = HSTU_BF16; n.dy = dy; n.sdy = HD; n.a = attn_saved; n.sa = HD; n.u = u_saved; n.su = HD;
+    n.gamma = p->gated_norm_w; n.beta = nullptr; n.eps = p->gated_norm_eps; n.da = dattn; n.sda = HD; n.du = dact; n.sdu = 4 * HD;
+    n.residual = nullptr; n.sres = 0; n.dgamma = d_gated_norm_w; n.dbeta = nullptr;
+    if (launch_norm_bwd(n, partial, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  }
+  {  // Eq. 1 again: the normalised input from the saved statistics (in bf16: the weight gradient needs it in any case)
     ProfScope ps("layer_norm_fwd", stream);
     NormFwdArgs n = {};
     n.T = T; n.D = (int32_t)E; n.dtype = HSTU_BF16; n.a = z; n.sa = E; n.u = nullptr; n.su = 0; n.gamma = p->norm_w; n.beta = nullptr;
@@ -255,28 +264,6 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
     ProfScope ps("silu_fwd", stream);
     if (launch_silu_fwd(T, (int)(4 * HD), pre, act, nullptr, 0, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
-  {  // out = Y W2^T + Z:  dY = dout W2,  dW2 = dout^T Y
-    ProfScope ps("gemm_dy", stream);
-    st = gemm_status(gemm_bf16(kGemmNN, T, HD, E, dout, E, p->w2, HD, nullptr, 0, dy, HD, false, gws, kGemmWorkspace, stream));
-    if (st != HSTU_OK) return st;
-  }
-  {  // weight gradients: this library's slab-split kernel when the widths are multiples of 128, else the GEMM library
-    ProfScope ps("gemm_dw2", stream);
-    if (gemm_tn_supported((int)E, (int)HD)) {
-      if (launch_gemm_tn(T, (int)E, (int)HD, dout, E, y, HD, d_w2, (float*)(ws + l.tn_partial), stream) != hipSuccess) return HSTU_ERR_LAUNCH;
-    } else {
-      st = gemm_status(gemm_bf16(kGemmTN, E, HD, T, dout, E, y, HD, nullptr, 0, d_w2, HD, true, gws, kGemmWorkspace, stream));
-      if (st != HSTU_OK) return st;
-    }
-  }
-  {  // gated norm backward: dA, dU (straight into the U block of the projection gradient), d gated_norm_w
-    ProfScope ps("gated_norm_bwd", stream);
-    NormBwdArgs n = {};
-    n.T = T; n.D = (int32_t)HD; n.dtype = HSTU_BF16; n.dy = dy; n.sdy = HD; n.a = attn_saved; n.sa = HD; n.u = u_saved; n.su = HD;
-    n.gamma = p->gated_norm_w; n.beta = nullptr; n.eps = p->gated_norm_eps; n.da = dattn; n.sda = HD; n.du = dact; n.sdu = 4 * HD;
-    n.residual = nullptr; n.sres = 0; n.dgamma = d_gated_norm_w; n.dbeta = nullptr;
-    if (launch_norm_bwd(n, partial, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
-  }
   // attention backward: dV, dQ, dK land in their column blocks, no concatenation
   st = hstu_attn_bwd(&ap, act + 2 * HD, act + 3 * HD, act + HD, dattn, dact + 2 * HD, dact + 3 * HD, dact + HD, ws + l.attn, l.attn_bytes,
                      stream_);
@@ -297,6 +284,21 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
         return HSTU_ERR_LAUNCH;
     } else {
       st = gemm_status(gemm_bf16(kGemmTN, 4 * HD, E, T, dact, 4 * HD, xn, E, nullptr, 0, d_w1, E, true, gws, kGemmWorkspace, stream));
+      if (st != HSTU_OK) return st;
+    }
+  }
+  {  // Eq. 4: Y from the saved A and U, for dW2 = dout^T Y
+    ProfScope ps("gated_norm_fwd", stream);
+    if (launch_gated_norm_fwd(T, (int)HD, HSTU_BF16, attn_saved, u_saved, p->gated_norm_w, nullptr, p->gated_norm_eps, y, nullptr, nullptr,
+                              stream) != hipSuccess)
+      return HSTU_ERR_LAUNCH;
+  }
+  {  // weight gradients: this library's slab-split kernel when the widths are multiples of 128, else the GEMM library
+    ProfScope ps("gemm_dw2", stream);
+    if (gemm_tn_supported((int)E, (int)HD)) {
+      if (launch_gemm_tn(T, (int)E, (int)HD, dout, E, y, HD, d_w2, (float*)(ws + l.tn_partial), stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    } else {
+      st = gemm_status(gemm_bf16(kGemmTN, E, HD, T, dout, E, y, HD, nullptr, 0, d_w2, HD, true, gws, kGemmWorkspace, stream));
       if (st != HSTU_OK) return st;
     }
   }
