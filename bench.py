@@ -27,14 +27,19 @@ PEAK_HBM_GBS = 8000.0
 ROOT = os.path.dirname(os.path.abspath(__file__))
 
 
+TRAFFIC_SOURCES = ("attn_core.hip", "attn_fwd_pipe.hip", "gated_norm.hip", "schedule.hip", "api.hip", "hstu_common.h", "hstu_geometry.h",
+                   "hstu_kernels.h")
+
+
 def kernel_sources_hash():
+    """Hash of the sources of the kernels whose traffic profiles/traffic.json holds (attention, gated norm, scheduler and the
+    entry points that launch them)."""
     import hashlib
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2602_16986_amd", "csrc")
-    for name in sorted(os.listdir(d)):
-        if name.endswith((".hip", ".h", ".cpp")):
-            h.update(name.encode())
-            h.update(open(os.path.join(d, name), "rb").read())
+    for name in TRAFFIC_SOURCES:
+        h.update(name.encode())
+        h.update(open(os.path.join(d, name), "rb").read())
     return h.hexdigest()
 
 
