@@ -65,6 +65,29 @@ def test_random_config_many_heads(seed):
     run_case(draw_many_heads(seed))
 
 
+def draw_pipelined(seed):
+    """bf16 with 128 features and sequences of up to 3,000 tokens: the software-pipelined kernels with tile lists long enough
+    for their steady state, lists that jump between the global prefix and the local band, prefixes that end inside a
+    32-key sub-block (patched seeds), candidate suffixes, and blocks cut into pieces."""
+    rng = np.random.default_rng(55_000 + seed)
+    B = int(rng.integers(1, 5))
+    L = rng.integers(1, int(rng.choice([700, 1600, 3000])) + 1, size=B)
+    H = int(rng.choice([1, 2, 3]))
+    K1 = int(rng.choice([-1, -1, 40, 250, 1000, 1024]))
+    K2 = int(rng.choice([0, 32, 33, 100, 513])) if K1 >= 0 else 0
+    targets = None
+    if rng.random() < 0.4:
+        targets = np.array([int(rng.integers(0, min(l, 150) + 1)) for l in L], dtype=np.int32)
+    alpha = 1.0 if rng.random() < 0.5 else float(rng.choice([0.5, 0.0884]))
+    return wl.build(f"pipe{seed}", L, H, 128, "bf16", rng=rng, bias=bool(rng.random() < 0.8), K1=K1, K2=K2, num_targets=targets,
+                    alpha=alpha, backward=True)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_config_pipelined_kernels(seed):
+    run_case(draw_pipelined(seed))
+
+
 # ----------------------------------------------------------------------------------------------
 # the entry points around the attention: whole layer (bf16 and FP8 forward), FP8 GEMM, truncation, query tail
 # ----------------------------------------------------------------------------------------------
