@@ -172,9 +172,6 @@ ProfScope::~ProfScope() {
 }
 }  // namespace hstu
 
-namespace {
-}  // namespace
-
 extern "C" {
 
 int hstu_profile_enable(int on) {
@@ -262,8 +259,23 @@ int hstu_attn_fwd(const hstu_attn_params* p, const void* q, const void* k, const
 
 int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const void* v, const void* dout, void* dq,
                   void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream_) {
+  return hstu::attn_bwd_through_silu(p, q, k, v, nullptr, nullptr, nullptr, 0, dout, dq, dk, dv, workspace, workspace_bytes, stream_);
+}
+
+}  // extern "C"
+
+int hstu::attn_bwd_through_silu(const hstu_attn_params* p, const void* q, const void* k, const void* v, const void* pre_q,
+                                const void* pre_k, const void* pre_v, int64_t s_pre, const void* dout, void* dq, void* dk,
+                                void* dv, void* workspace, size_t workspace_bytes, void* stream_) {
   const int st = validate(p);
   if (st != HSTU_OK) return st;
+  if (pre_q || pre_k || pre_v) {
+    if (p->dtype != HSTU_BF16) return HSTU_ERR_UNSUPPORTED;
+    if (!pre_q || !pre_k || !pre_v) return HSTU_ERR_NULL;
+    if (misaligned(pre_q) || misaligned(pre_k) || misaligned(pre_v) || s_pre % 8 != 0 ||
+        s_pre < (int64_t)p->num_heads * p->head_dim)
+      return HSTU_ERR_SHAPE;
+  }
   if (p->query_tail > 0) return HSTU_ERR_UNSUPPORTED;    // the query tail is a forward (inference) feature
   if (p->total_tokens == 0 || p->batch == 0) {           // no pairs: the only output that still exists is a zero table gradient
     if (p->d_rab_table &&
@@ -282,6 +294,7 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
 
   AttnArgs a = make_args(p, q, k, v);
   a.dout = dout; a.dq = dq; a.dk = dk; a.dv = dv;
+  a.pre_q = pre_q; a.pre_k = pre_k; a.pre_v = pre_v; a.s_pre = s_pre;
   const int tile = stream_tile_rows(p->dtype, p->head_dim);
   {
     ProfScope ps("bias_expand_bwd", stream);
@@ -326,6 +339,8 @@ int hstu_attn_bwd(const hstu_attn_params* p, const void* q, const void* k, const
   }
   return HSTU_OK;
 }
+
+extern "C" {
 
 int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, int for_backward, int64_t out[3]) {
   const int st = validate(p);

@@ -147,6 +147,12 @@ __device__ __forceinline__ void diag_all(std::integer_sequence<int, R...>, const
 // rows once the bias strip is addressed with the row's effective position (query-stationary passes) or anchored at n
 // for a tile of candidate queries (dK/dV pass).  Batches without candidates run the instantiation without it (a few
 // scalar instructions per tile less).
+// d/dt [t sigmoid(t)]
+__device__ __forceinline__ float dsilu(float t) {
+  const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-kLog2e * t));
+  return sg * (1.0f + t * (1.0f - sg));
+}
+
 template <typename E, int D, int MODE, int NWAVES, bool DBIAS = false, bool CAND = false>
 __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) void attn_kernel(const AttnArgs a) {
   static_assert(!DBIAS || MODE == kBwdDQ, "the bias gradient rides with the dQ pass");
@@ -1078,13 +1084,26 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     else if (o == 0) { dst = (E*)a.dk; sd = a.sk; scale = a.inv_n * a.alpha; }
     else { dst = (E*)a.dv; sd = a.sv; scale = a.inv_n * kLn2; }
     dst += (int64_t)(seq0 + x) * sd + hoff;
+    // the operand was SiLU(pre): hand back the gradient of pre
+    const __bf16* pre = nullptr;
+    if constexpr (C::kBf16 && MODE != kFwd) {
+      pre = (const __bf16*)(MODE == kBwdDQ ? a.pre_q : (o == 0 ? a.pre_k : a.pre_v));
+      if (pre) pre += (int64_t)(seq0 + x) * a.s_pre + hoff;
+    }
 #pragma unroll
     for (int ob = 0; ob < C::OB; ++ob)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int f = ob * 32 + 8 * q4 + 4 * hf;
-        const float v0 = out[o][ob][4 * q4 + 0] * scale, v1 = out[o][ob][4 * q4 + 1] * scale;
-        const float v2 = out[o][ob][4 * q4 + 2] * scale, v3 = out[o][ob][4 * q4 + 3] * scale;
+        float v0 = out[o][ob][4 * q4 + 0] * scale, v1 = out[o][ob][4 * q4 + 1] * scale;
+        float v2 = out[o][ob][4 * q4 + 2] * scale, v3 = out[o][ob][4 * q4 + 3] * scale;
+        if constexpr (C::kBf16 && MODE != kFwd) {
+          if (pre) {
+            const u32x2 t = *(const u32x2*)(pre + f);
+            v0 *= dsilu(__uint_as_float(t[0] << 16)); v1 *= dsilu(__uint_as_float(t[0] & 0xFFFF0000u));
+            v2 *= dsilu(__uint_as_float(t[1] << 16)); v3 *= dsilu(__uint_as_float(t[1] & 0xFFFF0000u));
+          }
+        }
         if constexpr (C::kBf16) {
           *(u32x2*)(dst + f) = (u32x2){pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
         } else {
@@ -1124,6 +1143,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttnArgs a, int bloc
     E* base = FWD ? (E*)a.out : (WHAT == kCombineDQ ? (E*)a.dq : (E*)(o == 0 ? a.dk : a.dv));
     const int64_t stride = FWD ? a.so : (WHAT == kCombineDQ ? a.sq : (o == 0 ? a.sk : a.sv));
     E* dst = base + (int64_t)(seq0 + x) * stride + (int64_t)h * D + 4 * c4;
+    if constexpr (sizeof(E) == 2 && !FWD) {
+      const __bf16* pre = (const __bf16*)(WHAT == kCombineDQ ? a.pre_q : (o == 0 ? a.pre_k : a.pre_v));
+      if (pre) {
+        const u32x2 t = *(const u32x2*)(pre + (int64_t)(seq0 + x) * a.s_pre + (int64_t)h * D + 4 * c4);
+        acc[0] *= dsilu(__uint_as_float(t[0] << 16)); acc[1] *= dsilu(__uint_as_float(t[0] & 0xFFFF0000u));
+        acc[2] *= dsilu(__uint_as_float(t[1] << 16)); acc[3] *= dsilu(__uint_as_float(t[1] & 0xFFFF0000u));
+      }
+    }
     if constexpr (sizeof(E) == 2) *(u32x2*)dst = (u32x2){pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
     else *(f32x4*)dst = acc;
   }

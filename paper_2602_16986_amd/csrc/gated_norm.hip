@@ -46,6 +46,17 @@ __device__ __forceinline__ void store8(E* row, int e0, const float (&v)[8]) {
     *(f32x4*)(row + e0 + 4) = (f32x4){v[4], v[5], v[6], v[7]};
   }
 }
+// v[i] *= d/dt [t sigmoid(t)] at t = pre[e0 + i]: the gradient passes back through a SiLU whose input is `pre`
+template <typename E>
+__device__ __forceinline__ void dsilu8(const E* pre, int e0, float (&v)[8]) {
+  float t[8];
+  load8(pre, e0, t);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * t[i]));
+    v[i] *= sg * (1.0f + t[i] * (1.0f - sg));
+  }
+}
 
 // mean and reciprocal standard deviation of one row held as NCH chunks of 8 per lane
 template <int NCH>
@@ -236,7 +247,10 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(const No
           m2 += dah[c][i] * ah;
           a[c][i] = ah;
         }
-        if (urow) store8((E*)p.du + row * p.sdu, e0, duv);
+        if (urow) {
+          if (p.du_pre) dsilu8((const E*)p.du_pre + row * p.sdu_pre, e0, duv);
+          store8((E*)p.du + row * p.sdu, e0, duv);
+        }
       }
     }
     m1 = wave_sum(m1) / (float)D;
@@ -351,7 +365,10 @@ __global__ __launch_bounds__(64 * W) void gated_norm_bwd_wide_kernel(const NormB
         bsum[i] += dn[i];
         dav[i] = rs * (dah[i] - m1 - ah * m2) + rv[i];     // rv: gradient that bypasses the norm (residual connection), else 0
       }
-      if (urow) store8((E*)p.du + row * p.sdu, e0, duv);
+      if (urow) {
+        if (p.du_pre) dsilu8((const E*)p.du_pre + row * p.sdu_pre, e0, duv);
+        store8((E*)p.du + row * p.sdu, e0, duv);
+      }
       store8((E*)p.da + row * p.sda, e0, dav);
     }
   }

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+struct hstu_attn_params;
+
 namespace hstu {
 
 // First 256 bytes of every attention workspace.
@@ -47,6 +49,9 @@ struct AttnArgs {
   const SplitItem* splits;
   int32_t query_tail;               // forward only, > 0: compute only the last query_tail history rows and the candidates of every sequence
   float* dbias_dist;                // dQ pass, optional: sum of dS per head and distance [H, bias_stride] (zeroed by the caller)
+  // optional (bf16 backward): q, k, v = SiLU(pre_q / pre_k / pre_v) [T, H, D] with row stride s_pre; dq, dk, dv then leave
+  // as the gradients of those pre-activations (multiplied by SiLU' on the way out)
+  const void* pre_q; const void* pre_k; const void* pre_v; int64_t s_pre;
   const int32_t* bucket_end;        // with dbias_dist: [bias_stride], the first distance of the bucket after the one that holds distance i (INT_MAX: none)
   // Score seeds of the pipelined kernels: bias and mask of a (position, key) pair as a function of the distance
   // d = position - key alone, [variant][H][seed_len] floats:  seed[i] <-> d = seed_dmax - i (descending distances, so that
@@ -88,6 +93,11 @@ int dkv_tile_rows(int dtype, int D);      // ... in the dK/dV pass
 hipError_t launch_attn_fwd(const AttnArgs& a, int dtype, hipStream_t stream);
 // attn_fwd_pipe.hip: the forward for bf16 and 128 features per head (same work lists as launch_attn_fwd: 128-row blocks, 32-key tiles)
 hipError_t launch_attn_fwd_pipe(const AttnArgs& a, hipStream_t stream);
+// hstu_attn_bwd for operands that are SiLU of pre-activations (bf16 only; pre_* [T, H, D] with row stride s_pre, all three
+// or none): dq, dk, dv leave as the gradients of the pre-activations.  Same checks and error codes as hstu_attn_bwd.
+int attn_bwd_through_silu(const hstu_attn_params* p, const void* q, const void* k, const void* v, const void* pre_q,
+                          const void* pre_k, const void* pre_v, int64_t s_pre, const void* dout, void* dq, void* dk, void* dv,
+                          void* workspace, size_t workspace_bytes, void* stream);
 hipError_t launch_attn_bwd_dq(const AttnArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_attn_bwd_dkdv(const AttnArgs& a, int dtype, hipStream_t stream);
 // bias-table gradient: clear the per-distance sums, fold them into buckets (times `scale`) after the dQ pass
@@ -121,6 +131,7 @@ struct NormBwdArgs {
   float eps;
   void* da; int64_t sda;
   void* du; int64_t sdu;
+  const void* du_pre; int64_t sdu_pre;      // optional: u = SiLU(du_pre); du then leaves as the gradient of du_pre (du * SiLU'(du_pre))
   const void* residual; int64_t sres;       // optional rows added to da (gradient of a residual connection)
   float* dgamma; float* dbeta;              // dbeta may be nullptr
 };
@@ -138,7 +149,7 @@ hipError_t launch_gated_norm_bwd(int64_t T, int D, int dtype, const void* dy, co
 
 
 // pointwise.hip: SiLU of the [T, C] projection (bf16, contiguous, C a multiple of 8) and its backward
-hipError_t launch_silu_fwd(int64_t T, int C, const void* pre, void* act, void* u_out, int u_cols, hipStream_t stream);
+hipError_t launch_silu_fwd(int64_t T, int C, const void* pre, void* act, void* u_out, int u_cols, hipStream_t stream, int skip_cols = 0);
 hipError_t launch_silu_bwd(int64_t T, int C, const void* pre, void* dact, hipStream_t stream);
 
 // gemm.hip: row-major bf16 products with fp32 accumulation through hipBLASLt.

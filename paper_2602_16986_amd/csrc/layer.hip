@@ -219,20 +219,12 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
   float* partial = (float*)(ws + l.norm_partial);
   void* gws = ws + l.gemm;
   const bool fp8 = p->w1_q != nullptr;
-  // Ordered by what each step needs, not by the forward's order: the gradient of the output projection and the gated norm's
-  // backward need only dout and the saved tensors, so they go first; Y is rebuilt last, right before the one product that reads it.
+  // Ordered by what each step needs, not by the forward's order; Y is rebuilt last, right before the one product that reads it.
+  // No kernel of its own for the SiLU backward: every producer of a projection gradient multiplies by SiLU' as it stores.
   {  // Eq. 5 / f2, out = Y W2^T + Z:  dY = dout W2
     ProfScope ps("gemm_dy", stream);
     st = gemm_status(gemm_bf16(kGemmNN, T, HD, E, dout, E, p->w2, HD, nullptr, 0, dy, HD, false, gws, kGemmWorkspace, stream));
     if (st != HSTU_OK) return st;
-  }
-  {  // Eq. 4 backward: dA, dU (straight into the U block of the projection gradient), d gated_norm_w
-    ProfScope ps("gated_norm_bwd", stream);
-    NormBwdArgs n = {};
-    n.T = T; n.D = (int32_t)HD; n.dtype = HSTU_BF16; n.dy = dy; n.sdy = HD; n.a = attn_saved; n.sa = HD; n.u = u_saved; n.su = HD;
-    n.gamma = p->gated_norm_w; n.beta = nullptr; n.eps = p->gated_norm_eps; n.da = dattn; n.sda = HD; n.du = dact; n.sdu = 4 * HD;
-    n.residual = nullptr; n.sres = 0; n.dgamma = d_gated_norm_w; n.dbeta = nullptr;
-    if (launch_norm_bwd(n, partial, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
   {  // Eq. 1 again: the normalised input from the saved statistics (in bf16: the weight gradient needs it in any case)
     ProfScope ps("layer_norm_fwd", stream);
@@ -260,18 +252,24 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
     st = gemm_status(gemm_bf16(kGemmNT, T, 4 * HD, E, xn, E, p->w1, E, nullptr, 0, pre, 4 * HD, false, gws, kGemmWorkspace, stream));
     if (st != HSTU_OK) return st;
   }
+  {  // Eq. 4 backward: dA, d gated_norm_w and, through U = SiLU(gate pre-activation), the gate block of the projection gradient
+    ProfScope ps("gated_norm_bwd", stream);
+    NormBwdArgs n = {};
+    n.T = T; n.D = (int32_t)HD; n.dtype = HSTU_BF16; n.dy = dy; n.sdy = HD; n.a = attn_saved; n.sa = HD; n.u = u_saved; n.su = HD;
+    n.gamma = p->gated_norm_w; n.beta = nullptr; n.eps = p->gated_norm_eps; n.da = dattn; n.sda = HD; n.du = dact; n.sdu = 4 * HD;
+    n.du_pre = pre; n.sdu_pre = 4 * HD;
+    n.residual = nullptr; n.sres = 0; n.dgamma = d_gated_norm_w; n.dbeta = nullptr;
+    if (launch_norm_bwd(n, partial, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+  }
   {
     ProfScope ps("silu_fwd", stream);
-    if (launch_silu_fwd(T, (int)(4 * HD), pre, act, nullptr, 0, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
+    // (V, Q, K only: the gate's activation is the saved tensor, nothing reads it from this buffer)
+    if (launch_silu_fwd(T, (int)(4 * HD), pre, act, nullptr, 0, stream, (int)HD) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
-  // attention backward: dV, dQ, dK land in their column blocks, no concatenation
-  st = hstu_attn_bwd(&ap, act + 2 * HD, act + 3 * HD, act + HD, dattn, dact + 2 * HD, dact + 3 * HD, dact + HD, ws + l.attn, l.attn_bytes,
-                     stream_);
+  // attention backward: the gradients of the V, Q, K pre-activations land in their column blocks (SiLU' applied on the way out)
+  st = attn_bwd_through_silu(&ap, act + 2 * HD, act + 3 * HD, act + HD, pre + 2 * HD, pre + 3 * HD, pre + HD, 4 * HD, dattn,
+                             dact + 2 * HD, dact + 3 * HD, dact + HD, ws + l.attn, l.attn_bytes, stream_);
   if (st != HSTU_OK) return st;
-  {
-    ProfScope ps("silu_bwd", stream);
-    if (launch_silu_bwd(T, (int)(4 * HD), pre, dact, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
-  }
   {  // pre = X W1^T:  dX = dpre W1,  dW1 = dpre^T X
     ProfScope ps("gemm_dxn", stream);
     st = gemm_status(gemm_bf16(kGemmNN, T, E, 4 * HD, dact, 4 * HD, p->w1, E, nullptr, 0, dxn, E, false, gws, kGemmWorkspace, stream));

@@ -24,21 +24,22 @@ __device__ __forceinline__ float sigmoidf_fast(float t) {
 }
 
 // act = pre * sigmoid(pre); `act` may be `pre` itself.  Columns [0, u_cols) of every row also go to u_out [T, u_cols]
-// (the gate is kept for the backward while the rest of the projection is dropped), when u_out is given.
-__global__ __launch_bounds__(kThreads) void silu_fwd_kernel(int64_t groups, int C8, const u32x4* pre, u32x4* act,
+// (the gate is kept for the backward while the rest of the projection is dropped), when u_out is given.  Columns before
+// skip8 (in 8-element groups) are neither read nor written (the backward rebuilds V, Q, K only: the gate was saved).
+__global__ __launch_bounds__(kThreads) void silu_fwd_kernel(int64_t groups, int C8, int skip8, const u32x4* pre, u32x4* act,
                                                             u32x4* __restrict__ u_out, int u8) {
-  for (int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x; g < groups; g += (int64_t)gridDim.x * kThreads) {
+  const int W8 = C8 - skip8;
+  for (int64_t gi = (int64_t)blockIdx.x * kThreads + threadIdx.x; gi < groups; gi += (int64_t)gridDim.x * kThreads) {
+    const int64_t row = gi / W8;
+    const int col = skip8 + (int)(gi - row * W8);
+    const int64_t g = row * C8 + col;
     float v[8];
     unpack8(pre[g], v);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] *= sigmoidf_fast(v[i]);
     const u32x4 o = pack8(v);
     act[g] = o;
-    if (u_out) {
-      const int64_t row = g / C8;
-      const int col = (int)(g - row * C8);
-      if (col < u8) u_out[row * u8 + col] = o;
-    }
+    if (u_out && col < u8) u_out[row * u8 + col] = o;
   }
 }
 
@@ -64,9 +65,10 @@ int blocks_for(int64_t groups) {
 
 }  // namespace
 
-hipError_t launch_silu_fwd(int64_t T, int C, const void* pre, void* act, void* u_out, int u_cols, hipStream_t stream) {
-  const int64_t groups = T * (C / 8);
-  hipLaunchKernelGGL(silu_fwd_kernel, dim3(blocks_for(groups)), dim3(kThreads), 0, stream, groups, C / 8, (const u32x4*)pre,
+hipError_t launch_silu_fwd(int64_t T, int C, const void* pre, void* act, void* u_out, int u_cols, hipStream_t stream, int skip_cols) {
+  const int64_t groups = T * ((C - skip_cols) / 8);
+  if (groups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(silu_fwd_kernel, dim3(blocks_for(groups)), dim3(kThreads), 0, stream, groups, C / 8, skip_cols / 8, (const u32x4*)pre,
                      (u32x4*)act, (u32x4*)u_out, u_cols / 8);
   return hipGetLastError();
 }
