@@ -167,13 +167,16 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   const int wg = blockIdx.x;
   const int xcd = wg % kNumXcd, slot = wg / kNumXcd;
   const int pos = ((slot / kXcdGroup) * kNumXcd + xcd) * kXcdGroup + slot % kXcdGroup;
-  if (pos >= a.header->count) return;
-  const WorkItem item = a.items[pos];
-  const int b = item.b, xb = item.rb_h >> 8, h = item.rb_h & 255;
+  // (the list's length and the entry are fetched together; an entry beyond the length is read, inside the list's
+  // capacity, and dropped)
+  const int count = a.header->count;
+  const WorkItem item = a.items[min(pos, a.max_items - 1)];
+  if (pos >= count) return;
+  const int xb = item.rb_h >> 8, h = item.rb_h & 255;
   const int t_begin = item.t0;
-  const int seq0 = a.offsets[b];
-  const int L = a.offsets[b + 1] - seq0;
-  const SeqGeom g = {L, L - (a.num_targets ? a.num_targets[b] : 0), a.K1, a.K2};
+  const int seq0 = item.seq0;
+  const int L = item.len;
+  const SeqGeom g = {L, item.hist, a.K1, a.K2};
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // scalar: per-wave decisions stay on the SALU
@@ -214,25 +217,34 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
       if constexpr (C::kBf16) {
         u32x4 raw = {0u, 0u, 0u, 0u};
         if (x_ok) raw = *(const u32x4*)(rp + ks * 16 + hf * 8);
-        if (i == 0) {                                                    // operand of the score product
-#pragma unroll
-          for (int w = 0; w < 4; ++w)
-            raw[w] = pack_bf16x2(__builtin_bit_cast(float, raw[w] << 16) * score_scale,
-                                 __builtin_bit_cast(float, raw[w] & 0xFFFF0000u) * score_scale);
-        }
         res[i][ks] = __builtin_bit_cast(RFrag, raw);
       } else {
-        res[i][ks] = x_ok ? rp[2 * ks + hf] * (i == 0 ? score_scale : 1.0f) : 0.f;
+        res[i][ks] = x_ok ? rp[2 * ks + hf] : 0.f;
       }
     }
   }
-
-  // The resident operands must have landed before the tile loop: inside it the only global loads
-  // in flight are the next tile's, and nothing may force a wait on those before they are needed.
+  // (first use further down, after the first tile's loads are issued: the two round trips to memory overlap)
+  auto finish_resident = [&]() {
 #pragma unroll
-  for (int i = 0; i < C::NREG; ++i)
+    for (int ks = 0; ks < C::KS; ++ks) {                                 // operand of the score product
+      if constexpr (C::kBf16) {
+        u32x4 raw = __builtin_bit_cast(u32x4, res[0][ks]);
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+v"(res[i][ks]));
+        for (int w = 0; w < 4; ++w)
+          raw[w] = pack_bf16x2(__builtin_bit_cast(float, raw[w] << 16) * score_scale,
+                               __builtin_bit_cast(float, raw[w] & 0xFFFF0000u) * score_scale);
+        res[0][ks] = __builtin_bit_cast(RFrag, raw);
+      } else {
+        res[0][ks] *= score_scale;
+      }
+    }
+    // The resident operands must have landed before the tile loop: inside it the only global loads
+    // in flight are the next tile's, and nothing may force a wait on those before they are needed.
+#pragma unroll
+    for (int i = 0; i < C::NREG; ++i)
+#pragma unroll
+      for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+v"(res[i][ks]));
+  };
 
   f32x16 out[C::NOUT][C::OB];
 #pragma unroll
@@ -481,6 +493,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   }
   set_next(t_begin < ntiles ? tr.at(t_begin) : 0, t_begin < ntiles);
   gload(0);
+  finish_resident();
   lstore(0);
   __syncthreads();
 

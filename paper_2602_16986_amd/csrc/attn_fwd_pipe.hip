@@ -57,7 +57,8 @@ constexpr int kNoTile = 1 << 28;
 // see what each costs in time and in the clock the chip sustains.  1: the global -> LDS loads of the loop; 2: the two
 // transcendentals of SiLU; 4: the LDS reads of K / V fragments and seeds (16 / 32 / 64: those of K / of V / of the seeds
 // alone); 8: the matrix instructions; 128: the K fragments are read but a constant register goes into the product in
-// their place (the reads stay, the operand stops changing).  Every memory access an ablated build still makes is one
+// their place (the reads stay, the operand stops changing); 256: four neighbouring blocks stream the same K and V tiles
+// (those of the first of the four), which is what perfect sharing of a semi-local window in the L2 would look like.  Every memory access an ablated build still makes is one
 // the normal build makes.
 #ifndef HSTU_FWD_ABLATE
 #define HSTU_FWD_ABLATE 0
@@ -69,6 +70,20 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 x, bf16x8 y, f32x16 acc) {
   if constexpr (kNoMfma) { asm volatile("" :: "v"(x), "v"(y)); return acc; }
   else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc, 0, 0, 0);
 }
+
+// Measurement builds only: with HSTU_FWD_TIMELINE defined non-zero, the first lane of every workgroup records the 100 MHz
+// wall clock at its start, after the prologue's barrier, after the tile loop and after its stores, and the compute unit it
+// ran on; hstu_debug_fwd_timeline() copies the records of the last launch out (5 words per work item, in list order).
+#ifndef HSTU_FWD_TIMELINE
+#define HSTU_FWD_TIMELINE 0
+#endif
+#if HSTU_FWD_TIMELINE
+constexpr int kTimelineItems = 16384;
+__device__ uint64_t g_timeline[5 * kTimelineItems];
+#define HSTU_TL(k) do { if (threadIdx.x == 0 && pos < kTimelineItems) g_timeline[5 * pos + (k)] = wall_clock64(); } while (0)
+#else
+#define HSTU_TL(k) do { } while (0)
+#endif
 
 typedef __attribute__((address_space(3))) void* lds_void;
 typedef __attribute__((address_space(3))) short4v* lds_s4;
@@ -83,12 +98,23 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
   const int wg = blockIdx.x;
   const int xcd = wg % kNumXcd, slot_id = wg / kNumXcd;
   const int pos = ((slot_id / kXcdGroup) * kNumXcd + xcd) * kXcdGroup + slot_id % kXcdGroup;
-  if (pos >= a.header->count) return;
-  const WorkItem item = a.items[pos];
-  const int b = item.b, xb = item.rb_h >> 8, h = item.rb_h & 255;
-  const int seq0 = a.offsets[b];
-  const int L = a.offsets[b + 1] - seq0;
-  const SeqGeom g = {L, L - (a.num_targets ? a.num_targets[b] : 0), a.K1, a.K2};
+  const int count = a.header->count;                                   // (fetched together with the entry, which is dropped if beyond)
+  const WorkItem item = a.items[min(pos, a.max_items - 1)];
+  if (pos >= count) return;
+  HSTU_TL(0);
+#if HSTU_FWD_TIMELINE
+  if (threadIdx.x == 0 && pos < kTimelineItems) {
+    uint32_t hw;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    uint32_t xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    g_timeline[5 * pos + 4] = ((uint64_t)xcc << 32) | hw;
+  }
+#endif
+  const int xb = item.rb_h >> 8, h = item.rb_h & 255;
+  const int seq0 = item.seq0;
+  const int L = item.len;
+  const SeqGeom g = {L, item.hist, a.K1, a.K2};
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -109,18 +135,26 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
   for (int ks = 0; ks < 8; ++ks) {
     u32x4 raw = {0u, 0u, 0u, 0u};
     if (x_ok) raw = *(const u32x4*)(Qp + (int64_t)x * a.sq + ks * 16 + hf * 8);
-#pragma unroll
-    for (int w = 0; w < 4; ++w)
-      raw[w] = pack_bf16x2(__builtin_bit_cast(float, raw[w] << 16) * score_scale,
-                           __builtin_bit_cast(float, raw[w] & 0xFFFF0000u) * score_scale);
     qf[ks] = __builtin_bit_cast(bf16x8, raw);
   }
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));      // landed before the loop: nothing in it may wait on them
   typedef __attribute__((address_space(3))) bf16x8* lds_b8w;
   const int qaddr = (int)(uint32_t)(uintptr_t)(lds_void)smem + kQBase + tid * 16;
+  // (first use in the prologue, after the first sub-blocks' loads are issued: the two round trips to memory overlap)
+  auto finish_q = [&]() {
 #pragma unroll
-  for (int i = 0; i < kQLds; ++i) *(lds_b8w)(uintptr_t)(uint32_t)(qaddr + i * kThreads * 16) = qf[8 - kQLds + i];
+    for (int ks = 0; ks < 8; ++ks) {
+      u32x4 raw = __builtin_bit_cast(u32x4, qf[ks]);
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        raw[w] = pack_bf16x2(__builtin_bit_cast(float, raw[w] << 16) * score_scale,
+                             __builtin_bit_cast(float, raw[w] & 0xFFFF0000u) * score_scale);
+      qf[ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));    // landed before the loop: nothing in it may wait on them
+#pragma unroll
+    for (int i = 0; i < kQLds; ++i) *(lds_b8w)(uintptr_t)(uint32_t)(qaddr + i * kThreads * 16) = qf[8 - kQLds + i];
+  };
 
   f32x16 out[4];
 #pragma unroll
@@ -144,10 +178,14 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
   const bool has_ps = straddle_t >= tr.a0 && straddle_t < tr.a1 && ps_raw >= t_begin && ps_raw < suf0;
   const int ps = has_ps ? ps_raw : kNoTile;
   const int nfast = (suf0 - t_begin) - (has_ps ? 1 : 0);
+  // (measurement build 256: the block streams the tiles of the first block of its aligned group of four)
+  const int x0m = (xb & ~3) * kBX;
+  const int mshift = tr.b0 - tile_ranges(g, x0m, min(x0m + kBX, L) - 1, kBN).b0;
   auto tile_of = [&](int idx) -> int {                                  // idx-th sub-block of the reordered list
     int p;
     if (idx < nfast) { p = t_begin + idx; p += (p >= ps) ? 1 : 0; }
     else { const int j = idx - nfast; p = (suf0 + j < t_end) ? suf0 + j : ps_raw; }
+    if constexpr ((HSTU_FWD_ABLATE & 256) != 0) { const int yt = tr.at(p); return yt >= tr.b0 ? yt - mshift : yt; }
     return tr.at(p);
   };
 
@@ -301,8 +339,10 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
     const Src none = src_of(n);
     load_v(none, 1, 0); load_v(none, 1, 1);
   }
+  finish_q();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  HSTU_TL(1);
 #pragma unroll
   for (int i = 0; i < kPF; ++i) kfn[i] = kfrag(0, i);
   seed(sacc[0], 0);
@@ -400,6 +440,7 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
     step(s + 1, IC<1>{}, std::true_type{});
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                      // nothing may still be landing in LDS when the wave ends
+  HSTU_TL(2);
 
   // ---- epilogue.  Lane x holds features 32 ob + 8 (r / 4) + 4 hf + r % 4.
   if (item.slot >= 0) {                                                 // a piece of a cut block: raw sums, the combine kernel finishes
@@ -410,9 +451,10 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
       for (int q4 = 0; q4 < 4; ++q4)
         *(f32x4*)(dst + ob * 32 + 8 * q4 + 4 * hf) =
             (f32x4){out[ob][4 * q4 + 0], out[ob][4 * q4 + 1], out[ob][4 * q4 + 2], out[ob][4 * q4 + 3]};
+    HSTU_TL(3);
     return;
   }
-  if (!x_ok || x < q0) return;
+  if (!x_ok || x < q0) { HSTU_TL(3); return; }
   const float scale = a.inv_n * kLn2;
   __bf16* dst = (__bf16*)a.out + (int64_t)(seq0 + x) * a.so + hoff;
 #pragma unroll
@@ -423,6 +465,10 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_pipe_kernel(const AttnAr
       *(u32x2*)(dst + f) = (u32x2){pack_bf16x2(out[ob][4 * q4 + 0] * scale, out[ob][4 * q4 + 1] * scale),
                                     pack_bf16x2(out[ob][4 * q4 + 2] * scale, out[ob][4 * q4 + 3] * scale)};
     }
+#if HSTU_FWD_TIMELINE
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  HSTU_TL(3);
+#endif
 }
 
 }  // namespace
@@ -439,3 +485,14 @@ hipError_t launch_attn_fwd_pipe(const AttnArgs& a, hipStream_t stream) {
 }
 
 }  // namespace hstu
+
+#if HSTU_FWD_TIMELINE
+// out: 5 * items words (start, prologue done, loop done, stores done in 10 ns ticks; hardware id); returns the number of items copied
+extern "C" int hstu_debug_fwd_timeline(uint64_t* out, int items) {
+  const int n = items < hstu::kTimelineItems ? items : hstu::kTimelineItems;
+  if (n <= 0 || !out) return 0;
+  if (hipDeviceSynchronize() != hipSuccess) return -1;
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(hstu::g_timeline), (size_t)n * 5 * sizeof(uint64_t), 0, hipMemcpyDeviceToHost) != hipSuccess) return -1;
+  return n;
+}
+#endif

@@ -23,7 +23,8 @@ struct WorkItem {
   int32_t rb_h;           // (block index << 8) | head
   int32_t t0, t1;         // positions [t0, min(t1, tiles of the block)) of the block's tile list
   int32_t slot;           // partial-sum slot of a piece, -1: the item writes its block's output itself
-  int32_t pad;
+  // the item's sequence, copied here so that a workgroup's first loads do not wait for a look-up by b:
+  int32_t seq0, len, hist;   // first token row, length, history length (length minus candidates)
 };
 
 struct SplitItem {        // a row block whose pieces left partial sums in slots [first_slot, first_slot + pieces)

@@ -185,7 +185,8 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
       locate(idx, H, b, rb, h, cost, dense, true);
       my_tiles += cost;
       my_dense += dense;
-      items[idx] = WorkItem{b, (rb << 8) | h, 0, 0x7FFFFFFF, -1, 0};
+      const int Lb = offsets[b + 1] - offsets[b];
+      items[idx] = WorkItem{b, (rb << 8) | h, 0, 0x7FFFFFFF, -1, offsets[b], Lb, Lb - (num_targets ? num_targets[b] : 0)};
     }
   }
   for (int off = 32; off > 0; off >>= 1) {                 // one LDS atomic per wave, not per thread
@@ -315,8 +316,10 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     int b, rb, h, cost = 0, dense;
     locate(idx, 1, b, rb, h, cost, dense, cut);
     const int pieces = cut ? pieces_of(cost, chunk) : 1, plen = piece_len(cost, pieces, chunk);
-    items[e] = cut ? WorkItem{b, (rb << 8) | hh, c * plen, min((c + 1) * plen, cost), (int)slot_c[idx] * H + hh * pieces + c, 0}
-                   : WorkItem{b, (rb << 8) | hh, 0, 0x7FFFFFFF, -1, 0};
+    const int sq0 = offsets[b], Lb = cached ? len_c[b] : offsets[b + 1] - sq0;
+    const int hist = cached ? hist_c[b] : Lb - (num_targets ? num_targets[b] : 0);
+    items[e] = cut ? WorkItem{b, (rb << 8) | hh, c * plen, min((c + 1) * plen, cost), (int)slot_c[idx] * H + hh * pieces + c, sq0, Lb, hist}
+                   : WorkItem{b, (rb << 8) | hh, 0, 0x7FFFFFFF, -1, sq0, Lb, hist};
   }
 }
 

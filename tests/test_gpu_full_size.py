@@ -140,7 +140,7 @@ def test_full_size_work_lists(name):
     torch.cuda.synchronize()
     st = hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)
     n = st["items"]
-    items = dw.ws_fwd[256:256 + 24 * n].cpu().numpy().view(np.int32).reshape(n, 6)
+    items = dw.ws_fwd[256:256 + 32 * n].cpu().numpy().view(np.int32).reshape(n, 8)
     BM, BN = 128, 32
     count = {}
     for b, L in enumerate(w.lengths.tolist()):
@@ -149,7 +149,10 @@ def test_full_size_work_lists(name):
             count[(b, rb)] = len(_visible_tiles(L, M, w.K1, w.K2, rb * BM, min(rb * BM + BM, L) - 1, BN))
     assert st["tiles"] == sum(count.values()) * w.H
     cover = {}
-    for b, rbh, t0, t1, slot, _ in items.tolist():
+    for b, rbh, t0, t1, slot, seq0, length, hist in items.tolist():
+        # every entry carries its sequence's first row, length and history length
+        M = 0 if w.num_targets is None else int(w.num_targets[b])
+        assert (seq0, length, hist) == (int(w.offsets[b]), int(w.lengths[b]), int(w.lengths[b]) - M)
         cover.setdefault((b, rbh >> 8, rbh & 255), []).append((t0, min(t1, count[(b, rbh >> 8)]), slot))
     assert set(cover) == {(b, rb, h) for (b, rb) in count for h in range(w.H)}
     slots = [x[2] for v in cover.values() for x in v if x[2] >= 0]
@@ -159,7 +162,7 @@ def test_full_size_work_lists(name):
         assert v[0][0] == 0 and v[-1][1] == count[(b, rb)] and all(x[1] == y[0] for x, y in zip(v, v[1:])), (b, rb, h, v)
         assert (len(v) == 1) == (v[0][2] < 0)
     # longest first: the cost of the list's entries (one per group of 4 x H items) never increases
-    cost = [min(t1, count[(b, rbh >> 8)]) - t0 for b, rbh, t0, t1, slot, _ in items.tolist()]
+    cost = [min(t1, count[(b, rbh >> 8)]) - t0 for b, rbh, t0, t1, slot, *_ in items.tolist()]
     G = 4 * w.H
     firsts = [max(cost[i:i + G]) for i in range(0, n, G)]
     lasts = [min(cost[i:i + G]) for i in range(0, n, G)]
@@ -182,7 +185,7 @@ def test_more_blocks_than_the_scheduler_sorts():
     dw.attn_fwd()
     torch.cuda.synchronize()
     st = hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)
-    items = dw.ws_fwd[256:256 + 24 * st["items"]].cpu().numpy().view(np.int32).reshape(-1, 6)
+    items = dw.ws_fwd[256:256 + 32 * st["items"]].cpu().numpy().view(np.int32).reshape(-1, 8)
     seen = sorted((int(b), int(rbh) >> 8, int(rbh) & 255) for b, rbh, *_ in items)
     assert seen == sorted((b, rb, 0) for b, L in enumerate(lengths) for rb in range((L + 127) // 128))
     assert (items[:, 4] < 0).all(), "no cuts expected on the unsorted path"

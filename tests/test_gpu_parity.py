@@ -309,10 +309,10 @@ def test_schedule_is_a_longest_first_permutation(hb):
         torch.cuda.synchronize()
         st = hb.hstu_attn_schedule_stats(dw.problem, dw.ws_fwd, False)
         n = st["items"]
-        items = dw.ws_fwd[256:256 + 24 * n].cpu().numpy().view(np.int32).reshape(n, 6)
+        items = dw.ws_fwd[256:256 + 32 * n].cpu().numpy().view(np.int32).reshape(n, 8)
         BM = 128
         full = lambda b, rb: (min((rb + 1) * BM, lengths[b]) - 1) // 32 + 1
-        got = [(int(b), int(rbh) >> 8, int(rbh) & 255, int(t0), int(t1), int(slot)) for b, rbh, t0, t1, slot, _ in items]
+        got = [(int(b), int(rbh) >> 8, int(rbh) & 255, int(t0), int(t1), int(slot)) for b, rbh, t0, t1, slot, *_ in items]
         assert n % w.H == 0
         # every block covered exactly once
         cover = {}
