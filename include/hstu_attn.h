@@ -349,7 +349,7 @@ int hstu_attn_schedule_stats(const hstu_attn_params* p, const void* workspace, i
  * written: names[i] (static strings: "attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "gated_norm_fwd",
  * "gated_norm_bwd" [the latter includes its column-sum kernel], "schedule_fwd", "schedule_bwd" [both backward lists, one launch], "bias_expand", "dbias_zero", "dbias_reduce",
  * "truncate_offsets", "truncate_fwd", "truncate_bwd", and from the layer entry points "layer_norm_fwd",
- * "gemm_uvqk", "silu_fwd", "gemm_out", "gemm_dy", "gemm_dw2", "silu_bwd", "gemm_dxn", "gemm_dw1", "layer_norm_bwd",
+ * "gemm_uvqk", "silu_fwd", "gemm_out", "gemm_dy", "gemm_dw2", "gemm_dxn", "gemm_dw1", "layer_norm_bwd",
  * and "norm_quant_fp8", "fp8_gemm_bias2d";
  * "attn_bwd_dkdv" includes the kernel that combines the partial sums of cut key blocks) and
  * ms[i] = elapsed milliseconds.  HOST arrays.  Not thread-safe; enable(1) creates the events once. */
