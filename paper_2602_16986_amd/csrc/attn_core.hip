@@ -30,9 +30,24 @@
 #define HSTU_DKDV_PF 2
 #endif
 
+// Measurement builds only: with HSTU_BWD_TIMELINE defined non-zero, the first lane of every workgroup of the two backward
+// passes records the 100 MHz wall clock at its start, after the prologue's barrier, after the tile loop and after its
+// stores; hstu_debug_bwd_timeline() copies the records of the last launch out (5 words per work item, in list order).
+#ifndef HSTU_BWD_TIMELINE
+#define HSTU_BWD_TIMELINE 0
+#endif
+
 namespace hstu {
 
 enum { kFwd = 0, kBwdDQ = 1, kBwdDKDV = 2 };
+
+#if HSTU_BWD_TIMELINE
+constexpr int kTimelineItems = 16384;
+__device__ uint64_t g_timeline_bwd[2][5 * kTimelineItems];
+#define HSTU_TLB(k) do { if (MODE != kFwd && threadIdx.x == 0 && pos < kTimelineItems) g_timeline_bwd[MODE == kBwdDQ ? 0 : 1][5 * pos + (k)] = wall_clock64(); } while (0)
+#else
+#define HSTU_TLB(k) do { } while (0)
+#endif
 
 template <typename E, int D, int MODE, int NWAVES>
 struct Cfg {
@@ -172,6 +187,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   const int count = a.header->count;
   const WorkItem item = a.items[min(pos, a.max_items - 1)];
   if (pos >= count) return;
+  HSTU_TLB(0);
   const int xb = item.rb_h >> 8, h = item.rb_h & 255;
   const int t_begin = item.t0;
   const int seq0 = item.seq0;
@@ -496,6 +512,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
   finish_resident();
   lstore(0);
   __syncthreads();
+  HSTU_TLB(1);
 
   const bool stat_hist = min(xw0 + 32, L) - 1 < g.n;  // this wave's stationary rows are all history rows
   constexpr int NSB = C::BN / 32;                     // 32-row sub-blocks of a streamed tile
@@ -1070,6 +1087,7 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
     if (ntiles > t_begin && !prev_fast) dacc_flush((ntiles - 1 - t_begin) & 1, tr.at(ntiles - 1));
     run_flush();
   }
+  HSTU_TLB(2);
   // ---- epilogue: scale once, convert, store.  Lane x holds features ob*32 + 8*(r/4) + 4*hf + r%4.
   {
     if (item.slot >= 0) {
@@ -1083,10 +1101,11 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
           for (int q4 = 0; q4 < 4; ++q4)
             *(f32x4*)(dst + (int64_t)o * C::BX * D + ob * 32 + 8 * q4 + 4 * hf) =
                 (f32x4){out[o][ob][4 * q4 + 0], out[o][ob][4 * q4 + 1], out[o][ob][4 * q4 + 2], out[o][ob][4 * q4 + 3]};
+      HSTU_TLB(3);
       return;
     }
   }
-  if (!x_ok || x < q0) return;
+  if (!x_ok || x < q0) { HSTU_TLB(3); return; }
 #pragma unroll
   for (int o = 0; o < C::NOUT; ++o) {
     E* dst;
@@ -1124,6 +1143,10 @@ __global__ __launch_bounds__(64 * NWAVES, (Cfg<E, D, MODE, NWAVES>::kWgPerCu)) v
         }
       }
   }
+#if HSTU_BWD_TIMELINE
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  HSTU_TLB(3);
+#endif
 }
 
 // Adds the partial sums of one cut block in piece order (fixed order: deterministic), applies the output scale and
@@ -1307,3 +1330,16 @@ hipError_t launch_dq_combine(const AttnArgs& a, int dtype, int max_splits, hipSt
 }
 
 }  // namespace hstu
+
+#if HSTU_BWD_TIMELINE
+// out: 5 * items words per pass (0: dQ pass, 1: dK/dV pass): start, prologue done, loop done, stores done in 10 ns ticks
+extern "C" int hstu_debug_bwd_timeline(uint64_t* out, int items, int pass) {
+  const int n = items < hstu::kTimelineItems ? items : hstu::kTimelineItems;
+  if (n <= 0 || !out || pass < 0 || pass > 1) return 0;
+  if (hipDeviceSynchronize() != hipSuccess) return -1;
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(hstu::g_timeline_bwd), (size_t)n * 5 * sizeof(uint64_t),
+                          (size_t)pass * 5 * hstu::kTimelineItems * sizeof(uint64_t), hipMemcpyDeviceToHost) != hipSuccess)
+    return -1;
+  return n;
+}
+#endif

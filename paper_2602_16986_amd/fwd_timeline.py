@@ -1,12 +1,12 @@
-"""Where the forward kernel's workgroups spend their time: prologue, tile loop, epilogue, and how many are resident.
+"""Where the attention kernels' workgroups spend their time: prologue, tile loop, epilogue, and how many are resident.
 
 Needs a measurement build of the library that records the wall clock per work item:
 
-    python -m paper_2602_16986_amd.build --define HSTU_FWD_TIMELINE=1 --output /tmp/libhstu_timeline.so
+    python -m paper_2602_16986_amd.build --define HSTU_FWD_TIMELINE=1 --define HSTU_BWD_TIMELINE=1 --output /tmp/libhstu_timeline.so
     HSTU_ATTN_LIB=/tmp/libhstu_timeline.so python -m paper_2602_16986_amd.fwd_timeline C3-sparse C3-dense C4
 
-For every workload: one forward launch, then per work item the time from the workgroup's start to the barrier that ends
-its prologue, to the end of its tile loop and to the completion of its stores (100 MHz clock, 10 ns ticks), the number of
+For every workload: forward and backward launches, then for each of the three passes, per work item the time from the
+workgroup's start to the barrier that ends its prologue, to the end of its tile loop and to the completion of its stores (100 MHz clock, 10 ns ticks), the number of
 workgroups alive and inside their tile loop over 20 slices of the launch, and the loop time by quartile of start time.
 """
 import ctypes
@@ -27,15 +27,30 @@ def timeline(name: str) -> None:
     if not hasattr(lib, "hstu_debug_fwd_timeline"):
         raise SystemExit("this library was not built with HSTU_FWD_TIMELINE=1")
     lib.hstu_debug_fwd_timeline.argtypes = [ctypes.c_void_p, ctypes.c_int]
-    dw = DeviceWorkload(wl.config(name))
-    for _ in range(5):
+    w = wl.config(name)
+    dw = DeviceWorkload(w)
+    backward = hasattr(lib, "hstu_debug_bwd_timeline") and w.dout is not None
+    for _ in range(20):
         dw.attn_fwd()
+        if backward:
+            dw.attn_bwd()
     torch.cuda.synchronize()
     buf = np.zeros(5 * MAX_ITEMS, dtype=np.uint64)
     if lib.hstu_debug_fwd_timeline(buf.ctypes.data, MAX_ITEMS) < 0:
         raise SystemExit("reading the timeline failed")
-    t = buf.reshape(MAX_ITEMS, 5)
+    report(name + " forward", buf.reshape(MAX_ITEMS, 5).copy())
+    if backward:
+        lib.hstu_debug_bwd_timeline.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int]
+        for which, label in ((0, "dQ pass"), (1, "dK/dV pass")):
+            buf[:] = 0
+            if lib.hstu_debug_bwd_timeline(buf.ctypes.data, MAX_ITEMS, which) < 0:
+                raise SystemExit("reading the timeline failed")
+            report(f"{name} {label}", buf.reshape(MAX_ITEMS, 5).copy())
+
+
+def report(name: str, t: np.ndarray) -> None:
     t = t[t[:, 0] > 0]
+    t = t[t[:, 0] + 1_000_000 > t[:, 0].max()]           # drop what an earlier workload left beyond this list's length (10 ms window)
     base = int(t[:, 0].min())
     start, loop0, loop1, end = [(t[:, i].astype(np.int64) - base) / 100.0 for i in range(4)]      # microseconds
     span = end.max()
