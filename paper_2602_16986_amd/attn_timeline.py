@@ -3,7 +3,7 @@
 Needs a measurement build of the library that records the wall clock per work item:
 
     python -m paper_2602_16986_amd.build --define HSTU_FWD_TIMELINE=1 --define HSTU_BWD_TIMELINE=1 --output /tmp/libhstu_timeline.so
-    HSTU_ATTN_LIB=/tmp/libhstu_timeline.so python -m paper_2602_16986_amd.fwd_timeline C3-sparse C3-dense C4
+    HSTU_ATTN_LIB=/tmp/libhstu_timeline.so python -m paper_2602_16986_amd.attn_timeline C3-sparse C3-dense C4
 
 For every workload: forward and backward launches, then for each of the three passes, per work item the time from the
 workgroup's start to the barrier that ends its prologue, to the end of its tile loop and to the completion of its stores (100 MHz clock, 10 ns ticks), the number of
