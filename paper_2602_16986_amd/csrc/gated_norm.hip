@@ -232,14 +232,16 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(const No
     for (int c = 0; c < NCH; ++c) {
       const int e0 = (lane + 64 * c) * 8;
       if (e0 < D) {
-        float dyv[8], uv[8], duv[8];
+        float dyv[8], uv[8], duv[8], yv[8];
         load8(dyrow, e0, dyv);
         if (urow) load8(urow, e0, uv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float ah = (a[c][i] - mu) * rs;
           const float dn = urow ? dyv[i] * uv[i] : dyv[i];
-          duv[i] = dyv[i] * (ah * gv[c][i] + bv[c][i]);
+          const float nv = ah * gv[c][i] + bv[c][i];
+          duv[i] = dyv[i] * nv;
+          yv[i] = urow ? nv * uv[i] : nv;
           gsum[c][i] += dn * ah;
           bsum[c][i] += dn;
           dah[c][i] = dn * gv[c][i];
@@ -250,6 +252,7 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(const No
         if (urow) {
           if (p.du_pre) dsilu8((const E*)p.du_pre + row * p.sdu_pre, e0, duv);
           store8((E*)p.du + row * p.sdu, e0, duv);
+          if (p.y_out) store8((E*)p.y_out + row * p.sy_out, e0, yv);
         }
       }
     }
@@ -336,10 +339,11 @@ __global__ __launch_bounds__(64 * W) void gated_norm_bwd_wide_kernel(const NormB
 #pragma unroll
     for (int w = 0; w < W; ++w) tot += red1[par][w];
     const float mu = tot * inv_d;
-    float q = 0.f, s1 = 0.f, s2 = 0.f, dah[8];
+    float q = 0.f, s1 = 0.f, s2 = 0.f, dah[8], uk[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float c = on ? a[i] - mu : 0.f;
+      uk[i] = dn[i];                                   // the gate, for the optional Y output
       dn[i] = urow ? dyv[i] * dn[i] : dyv[i];
       dah[i] = dn[i] * gv[i];
       q += c * c;
@@ -356,11 +360,13 @@ __global__ __launch_bounds__(64 * W) void gated_norm_bwd_wide_kernel(const NormB
     const float rs = 1.0f / sqrtf(tq * inv_d + p.eps);
     const float m1 = t1 * inv_d, m2 = rs * t2 * inv_d;
     if (on) {
-      float duv[8], dav[8];
+      float duv[8], dav[8], yv[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const float ah = a[i] * rs;
-        duv[i] = dyv[i] * (ah * gv[i] + bv[i]);
+        const float nv = ah * gv[i] + bv[i];
+        duv[i] = dyv[i] * nv;
+        yv[i] = nv * uk[i];
         gsum[i] += dn[i] * ah;
         bsum[i] += dn[i];
         dav[i] = rs * (dah[i] - m1 - ah * m2) + rv[i];     // rv: gradient that bypasses the norm (residual connection), else 0
@@ -368,6 +374,7 @@ __global__ __launch_bounds__(64 * W) void gated_norm_bwd_wide_kernel(const NormB
       if (urow) {
         if (p.du_pre) dsilu8((const E*)p.du_pre + row * p.sdu_pre, e0, duv);
         store8((E*)p.du + row * p.sdu, e0, duv);
+        if (p.y_out) store8((E*)p.y_out + row * p.sy_out, e0, yv);
       }
       store8((E*)p.da + row * p.sda, e0, dav);
     }

@@ -132,6 +132,7 @@ struct NormBwdArgs {
   float eps;
   void* da; int64_t sda;
   void* du; int64_t sdu;
+  void* y_out; int64_t sy_out;              // optional (with a gate): the forward's output Y = (LN(a) gamma + beta) * u, rebuilt along the way
   const void* du_pre; int64_t sdu_pre;      // optional: u = SiLU(du_pre); du then leaves as the gradient of du_pre (du * SiLU'(du_pre))
   const void* residual; int64_t sres;       // optional rows added to da (gradient of a residual connection)
   float* dgamma; float* dbeta;              // dbeta may be nullptr

@@ -219,7 +219,7 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
   float* partial = (float*)(ws + l.norm_partial);
   void* gws = ws + l.gemm;
   const bool fp8 = p->w1_q != nullptr;
-  // Ordered by what each step needs, not by the forward's order; Y is rebuilt last, right before the one product that reads it.
+  // Ordered by what each step needs, not by the forward's order.
   // No kernel of its own for the SiLU backward: every producer of a projection gradient multiplies by SiLU' as it stores.
   {  // Eq. 5 / f2, out = Y W2^T + Z:  dY = dout W2
     ProfScope ps("gemm_dy", stream);
@@ -252,12 +252,14 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
     st = gemm_status(gemm_bf16(kGemmNT, T, 4 * HD, E, xn, E, p->w1, E, nullptr, 0, pre, 4 * HD, false, gws, kGemmWorkspace, stream));
     if (st != HSTU_OK) return st;
   }
-  {  // Eq. 4 backward: dA, d gated_norm_w and, through U = SiLU(gate pre-activation), the gate block of the projection gradient
+  {  // Eq. 4 backward: dA, d gated_norm_w and, through U = SiLU(gate pre-activation), the gate block of the projection gradient;
+     // the same pass rebuilds Y from the saved A and U
     ProfScope ps("gated_norm_bwd", stream);
     NormBwdArgs n = {};
     n.T = T; n.D = (int32_t)HD; n.dtype = HSTU_BF16; n.dy = dy; n.sdy = HD; n.a = attn_saved; n.sa = HD; n.u = u_saved; n.su = HD;
     n.gamma = p->gated_norm_w; n.beta = nullptr; n.eps = p->gated_norm_eps; n.da = dattn; n.sda = HD; n.du = dact; n.sdu = 4 * HD;
     n.du_pre = pre; n.sdu_pre = 4 * HD;
+    n.y_out = y; n.sy_out = HD;                            // Eq. 4 again: Y, for dW2 = dout^T Y further down
     n.residual = nullptr; n.sres = 0; n.dgamma = d_gated_norm_w; n.dbeta = nullptr;
     if (launch_norm_bwd(n, partial, stream) != hipSuccess) return HSTU_ERR_LAUNCH;
   }
@@ -284,12 +286,6 @@ int hstu_layer_bwd(const hstu_layer_params* p, const void* z, const void* u_save
       st = gemm_status(gemm_bf16(kGemmTN, 4 * HD, E, T, dact, 4 * HD, xn, E, nullptr, 0, d_w1, E, true, gws, kGemmWorkspace, stream));
       if (st != HSTU_OK) return st;
     }
-  }
-  {  // Eq. 4: Y from the saved A and U, for dW2 = dout^T Y
-    ProfScope ps("gated_norm_fwd", stream);
-    if (launch_gated_norm_fwd(T, (int)HD, HSTU_BF16, attn_saved, u_saved, p->gated_norm_w, nullptr, p->gated_norm_eps, y, nullptr, nullptr,
-                              stream) != hipSuccess)
-      return HSTU_ERR_LAUNCH;
   }
   {  // weight gradients: this library's slab-split kernel when the widths are multiples of 128, else the GEMM library
     ProfScope ps("gemm_dw2", stream);
