@@ -47,6 +47,24 @@ __device__ __forceinline__ void store8(E* row, int e0, const float (&v)[8]) {
   }
 }
 // v[i] *= d/dt [t sigmoid(t)] at t = pre[e0 + i]: the gradient passes back through a SiLU whose input is `pre`
+// 8 consecutive elements as loaded (one 16-byte chunk of bf16, two of fp32), widened when they are used
+template <typename E> struct Raw8;
+template <> struct Raw8<__bf16> { u32x4 w; };
+template <> struct Raw8<float> { f32x4 lo, hi; };
+__device__ __forceinline__ Raw8<__bf16> load8raw(const __bf16* row, int e0) { return {*(const u32x4*)(row + e0)}; }
+__device__ __forceinline__ Raw8<float> load8raw(const float* row, int e0) { return {*(const f32x4*)(row + e0), *(const f32x4*)(row + e0 + 4)}; }
+__device__ __forceinline__ void widen8(const Raw8<__bf16>& r, float (&v)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(r.w[i] << 16);
+    v[2 * i + 1] = __uint_as_float(r.w[i] & 0xFFFF0000u);
+  }
+}
+__device__ __forceinline__ void widen8(const Raw8<float>& r, float (&v)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { v[i] = r.lo[i]; v[4 + i] = r.hi[i]; }
+}
+
 template <typename E>
 __device__ __forceinline__ void dsilu8(const E* pre, int e0, float (&v)[8]) {
   float t[8];
@@ -195,7 +213,7 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void norm_quant_fwd_kernel(cons
 // dbeta = sum dn are kept per lane over the rows a wave visits, combined across the workgroup's
 // waves in a fixed order through LDS and written as one partial row per workgroup.
 template <typename E, int NCH>
-__global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(const NormBwdArgs p, float* __restrict__ partial) {
+__global__ __launch_bounds__(64 * kBwdWaves, 4) void gated_norm_bwd_kernel(const NormBwdArgs p, float* __restrict__ partial) {
   extern __shared__ float red[];                       // [2][D]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int D = p.D;
@@ -219,10 +237,14 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(const No
     const E* urow = p.u ? (const E*)p.u + row * p.su : nullptr;         // no gate: plain layer norm, no dU
     const E* rrow = p.residual ? (const E*)p.residual + row * p.sres : nullptr;
     float a[NCH][8];
+    Raw8<E> rraw[NCH];                                 // the residual's rows travel with the first loads, not after the reductions
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       const int e0 = (lane + 64 * c) * 8;
-      if (e0 < D) load8(arow, e0, a[c]);
+      if (e0 < D) {
+        load8(arow, e0, a[c]);
+        if (rrow) rraw[c] = load8raw(rrow, e0);
+      }
     }
     float mu, rs;
     row_stats<NCH>(a, lane, D, p.eps, mu, rs);
@@ -263,7 +285,7 @@ __global__ __launch_bounds__(64 * kBwdWaves) void gated_norm_bwd_kernel(const No
       const int e0 = (lane + 64 * c) * 8;
       if (e0 < D) {
         float dav[8], rv[8];
-        if (rrow) load8(rrow, e0, rv);
+        if (rrow) widen8(rraw[c], rv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           dav[i] = rs * (dah[c][i] - m1 - a[c][i] * m2);
