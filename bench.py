@@ -316,16 +316,16 @@ def bench_layer(args):
 
 
 def other_configs(args, torch, hb, flops, workloads, DeviceWorkload, peak):
-    """Short timed steps of the configurations the headline is not quoted on: the same step loop, fewer steps."""
+    """Short timed steps of the configurations the headline is not quoted on: the same step loop, 10 warm-up and 30 timed steps."""
     res = {}
     for name in ("C3-sparse", "C4", "C5", "C2"):
         w = workloads.config(name)
         fl = flops.attention_flops(w)
         dw = DeviceWorkload(w)
         step = dw.layer_step if w.backward else dw.attn_fwd
-        for _ in range(3):
+        for _ in range(10):                       # (the chip idles while the host builds the inputs: let its clocks settle)
             step()
-        ms = time_loop(step, 10, torch)
+        ms = time_loop(step, 30, torch)
         hb.hstu_profile_enable(True)
         kern = {}
         for _ in range(5):
