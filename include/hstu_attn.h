@@ -205,8 +205,8 @@ int hstu_truncate_bwd(int32_t batch, int64_t total_tokens, const int32_t* seq_of
  *
  * The forward writes `out` and what the backward needs besides Z and the weights: u_saved [T, H*d],
  * attn_saved [T, H*d], mean and rstd of the input norm (fp32 [T]); V, Q, K, X and Y live in the workspace
- * and are dropped.  The backward rebuilds them (X from the saved statistics, U V Q K by the same GEMM, Y by
- * the gated norm) and returns dz [T, E] (including the residual's share) and fp32 d_norm_w [E],
+ * and are dropped.  The backward rebuilds them (X from the saved statistics, U V Q K by the same GEMM, Y inside
+ * the gated norm's backward) and returns dz [T, E] (including the residual's share) and fp32 d_norm_w [E],
  * d_w1 [4*H*d, E], d_gated_norm_w [H*d], d_w2 [E, H*d], all overwritten.  dU, dV, dQ, dK are written
  * straight into the column blocks of one gradient buffer (no concatenation).
  *
